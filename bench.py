@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the FeF-DLLM verify step on one MI355X.
+
+A step is one call of fef_verify_step (vocabulary head for draft and target rows, softmax,
+draft sampling, accept tests, first rejection, residual sample, commit, re-mask) on one batch
+of synthetic hidden states with the head W resident in HBM.  Prints ONE JSON line with the
+whole-step throughput (verify positions per second = B*K / step time), the roofline fraction
+of the dominant kernel (the vocabulary head, timed with HIP events recorded by the library
+around that kernel on its stream) and the CPU oracle timed on the host cores.
+
+    python bench.py [--gpus 1] [--steps 200] [--warmup 10] [--workload llada_b1]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+class HipEvents:
+    """Raw HIP events (ctypes on libamdhip64) so the library can record them on its stream."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        e = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(e))
+        assert rc == 0, f"hipEventCreate failed: {rc}"
+        return e.value
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventSynchronize(b)
+        assert rc == 0, f"hipEventSynchronize failed: {rc}"
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        assert rc == 0, f"hipEventElapsedTime failed: {rc}"
+        return ms.value
+
+    def destroy(self, e):
+        self.hip.hipEventDestroy(e)
+
+
+def head_bytes(wl, variant_tn):
+    """Algorithmic HBM bytes of one vocabulary-head launch: W once, H once, fp32 logits
+    written once, the per-tile (max, sum exp) partials."""
+    M = 2 * wl.B * wl.K
+    esz = 2 if wl.dtype == "bf16" else 4
+    nT = -(-wl.V // variant_tn)
+    return wl.V * wl.d * esz + M * wl.d * esz + M * wl.V * 4 + M * nT * 8
+
+
+def cpu_baseline(wl, W, rounds, seed, budget_s=20.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same rounds."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import fef_oracle as O
+    from paper_2605_14305_amd import synth
+    W64 = synth.to_f64(W)
+    nb = min(wl.B, max(1, 16 // wl.K))   # batched workloads: a leading subset of sequences
+    h64 = [(synth.to_f64(hd[:nb]), synth.to_f64(ht[:nb])) for hd, ht in rounds]
+    O.verify_step(h64[0][0], h64[0][1], W64, wl.K, wl.block, seed, temperature=wl.temperature)  # warm-up
+    n, t0 = 0, time.perf_counter()
+    while True:
+        hd, ht = h64[n % len(h64)]
+        O.verify_step(hd, ht, W64, wl.K, wl.block, seed, step=n, temperature=wl.temperature)
+        n += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or n >= 64:
+            break
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": nb * wl.K * n / el, "unit": "positions/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} verify steps of workload {wl.name} ({nb} of {wl.B} sequences, {nb * wl.K} positions each), "
+                      f"numpy fp64, {el:.1f} s; host has {len(os.sched_getaffinity(0))} usable cores"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llada_b1")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--events", choices=["inline", "separate"], default="inline",
+                    help="record the head-kernel events inside the timed steps, or in a second pass")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; the verify step shards over sequences with no "
+              "communication, and no multi-GPU figure is produced. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_14305_amd import binding as fb
+    from paper_2605_14305_amd import synth
+
+    wl = synth.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    W = synth.make_head(wl.V, wl.d, args.seed, wl.dtype)
+    Wd = W.to(dev)
+    n_rounds = 16   # distinct hidden-state batches, cycled, so only W could ever sit in a cache
+    rounds = [synth.make_round(wl, args.seed, block_index=i // 8, step=i) for i in range(n_rounds)]
+    rounds_d = [(hd.to(dev), ht.to(dev)) for hd, ht in rounds]
+
+    vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, dtype=wl.dtype, device=dev)
+    variant = fb.fef_select_gemm(vs._params(), wl.K)
+    tn = 16 if variant == fb.FEF_GEMM_SKINNY else 64
+    ev = HipEvents()
+    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+
+    def step(i, events=None):
+        hd, ht = rounds_d[i % n_rounds]
+        vs(hd, ht, Wd, args.seed, step=i, temperature=wl.temperature, head_events=events)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    inline = args.events == "inline"
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, pairs[i] if inline else None)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    if not inline:
+        for i in range(args.steps):
+            step(i, pairs[i])
+        torch.cuda.synchronize()
+    head_ms = [ev.elapsed_ms(a, b) for a, b in pairs]
+    head_avg_s = sum(head_ms) / len(head_ms) / 1e3
+
+    ms_per_step = elapsed / args.steps * 1e3
+    positions = wl.B * wl.K
+    M = 2 * positions
+    hb = head_bytes(wl, tn)
+    flops = 2.0 * M * wl.V * wl.d
+    hbm_time, mfma_time = hb / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if hbm_time >= mfma_time:
+        ach = hb / head_avg_s / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None}
+    else:
+        ach = flops / head_avg_s / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    roof.update({"kernel": {fb.FEF_GEMM_SKINNY: "head_skinny_kernel", fb.FEF_GEMM_TILED: "head_tiled_kernel",
+                            fb.FEF_GEMM_F32: "head_f32_kernel"}[variant],
+                 "avg_kernel_us": head_avg_s * 1e6, "algorithmic_bytes": hb, "flops": flops,
+                 "events": args.events})
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as f:
+            t = json.load(f).get(f"{roof['kernel']}:{wl.name}")
+        if t:
+            roof["traffic"] = t["hbm_bytes_per_launch"]
+
+    out = {
+        "metric": "verify-step positions/s at d=4096,V=126464 bf16; % HBM (B=1) / % MFMA (B>=32)",
+        "value": positions / (elapsed / args.steps),
+        "unit": "positions/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "K": wl.K, "block": wl.block, "d": wl.d, "V": wl.V,
+                   "rho": wl.rho, "logit_std": wl.logit_std, "temperature": wl.temperature,
+                   "rows_through_head": M},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, W, rounds, args.seed)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

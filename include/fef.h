@@ -1,0 +1,148 @@
+/* fef.h - C ABI of the FeF-DLLM speculative verify step for AMD Instinct MI355X (gfx950).
+ *
+ * One call = one speculative round of the paper's full-sequence decoding algorithm
+ * (Algorithm 2, body of the while-loop) for B independent sequences, followed by the
+ * low-confidence re-corruption of the same algorithm when the round resolves the block:
+ *
+ *   window      b = min{k, L}: the first k unresolved positions of the block, ascending
+ *   draft laws  rho^{j_m} = softmax(h_draft[m]  W^T / tau)
+ *   draft       x~^{j_m} ~ rho^{j_m}                        (inverse CDF, ascending token id)
+ *   target laws pi^{j_m}  = softmax(h_target[m] W^T / tau)
+ *   accept      u_m <= min{1, pi(x~)/rho(x~)}, left to right, stop at the first failure
+ *   correct     Z ~ [pi - rho]_+ / (1 - sum_z min{pi, rho})   (residual-distribution equation)
+ *   commit      token and confidence c = pi(token) for accepted slots and the corrected one
+ *   re-mask     if no unresolved position is left and this is not the final pass:
+ *               the n_rm committed positions of the pass with the lowest confidence return to
+ *               the corrupted (MASK) state
+ *
+ * The model forwards that produce the hidden states are outside the library.  The vocabulary
+ * head W is shared by both laws (the paper instantiates draft and target with one network).
+ *
+ * All random draws come from Philox4x32-10, key = (seed low, seed high), counter =
+ * (pos_base + block offset of the slot, step, seq_base + b, stream), output word 0,
+ * stream 0 = draft sample, 1 = accept test, 2 = residual sample; a word w becomes
+ * u = ((w >> 9) + 0.5) * 2^-23.  A call is therefore a pure function of its arguments.
+ *
+ * Conventions
+ *   - Plain C.  Every data pointer below is a DEVICE pointer owned by the caller unless it
+ *     says "host".  fef_params itself lives in host memory.
+ *   - The library allocates nothing: scratch space is the caller's `workspace`
+ *     (fef_workspace_bytes tells how much).  It keeps no state between calls.
+ *   - All work is enqueued on `stream`; the call returns without synchronising and the
+ *     outputs are valid in stream order.  Concurrent calls need distinct workspaces.
+ *   - Return value: FEF_OK or a negative fef_status.  Arguments are validated on the host
+ *     before anything is launched; on error nothing is enqueued and nothing is written.
+ *     fef_last_error() returns a thread-local description of the last failure.
+ *   - Limits: 1 <= K <= min(block, FEF_MAX_K); block <= FEF_MAX_BLOCK; B, V >= 1;
+ *     B*K <= 2^24; bf16: d a positive multiple of 64; f32: any d >= 1 and 2*B*K <= 65535.
+ *     Row offsets are 64-bit, so 2*B*K*V may exceed 2^31.
+ *     h_draft, h_target, W_vocab and workspace must be 16-byte aligned.
+ */
+#ifndef FEF_H
+#define FEF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FEF_MAX_K 64
+#define FEF_MAX_BLOCK 4096
+#define FEF_ABI_VERSION 1
+
+typedef enum {
+  FEF_OK = 0,
+  FEF_ERR_INVALID_ARG = -1, /* NULL / misaligned pointer, size or parameter out of range   */
+  FEF_ERR_UNSUPPORTED = -2, /* valid request that no kernel here serves                    */
+  FEF_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than fef_workspace_bytes          */
+  FEF_ERR_HIP = -4          /* a HIP runtime call failed (see fef_last_error)              */
+} fef_status;
+
+typedef enum {
+  FEF_BF16 = 0, /* h_draft, h_target, W_vocab are bfloat16; MFMA path                      */
+  FEF_F32 = 1   /* all three are float32; plain FMA path for tiny instances                */
+} fef_dtype;
+
+/* Which vocabulary-head kernel to run.  AUTO picks by (dtype, M = 2*B*K, d). */
+typedef enum {
+  FEF_GEMM_AUTO = 0,
+  FEF_GEMM_SKINNY = 1, /* bf16, M <= 16, d in {512, 3584, 4096}: W streamed once, split-k  */
+  FEF_GEMM_TILED = 2,  /* bf16, any M: LDS-tiled MFMA GEMM                                 */
+  FEF_GEMM_F32 = 3     /* f32, any shape: reference-grade FMA kernel                       */
+} fef_gemm_variant;
+
+typedef struct {
+  uint32_t struct_size;   /* = sizeof(fef_params); rejects callers built against another ABI */
+  int32_t B;              /* sequences in this call                                          */
+  int32_t d;              /* hidden size                                                     */
+  int32_t V;              /* vocabulary size (every id in [0, V) is a valid token)           */
+  int32_t dtype;          /* fef_dtype of h_draft, h_target, W_vocab                         */
+  float temperature;      /* tau > 0; both laws are softmax(logits / tau)                    */
+  uint32_t step;          /* index of this round; second Philox counter word                 */
+  uint32_t seq_base;      /* global index of sequence 0; third Philox counter word is +b     */
+  uint32_t pos_base;      /* absolute position of block offset 0; first counter word is +off */
+  int32_t n_rm;           /* re-mask budget of LowConf; < 0 means block / 2                  */
+  int32_t final_pass;     /* nonzero: last generation pass, no re-masking                    */
+  int32_t lowconf_scope;  /* 0: candidates = positions committed in this pass (pass_mask);
+                             1: every position of the block                                  */
+  int32_t gemm_variant;   /* fef_gemm_variant                                                */
+  const uint8_t* mask_in; /* [B, block] 1 = unresolved; NULL = whole block unresolved        */
+  uint8_t* pass_mask;     /* [B, block] in/out: committed in the current pass; NULL = empty  */
+  float* conf;            /* [B, block] in/out: confidence of resolved positions.  May be
+                             NULL only if pass_mask is NULL and lowconf_scope == 0           */
+  const int32_t* draft_tokens; /* [B, K] optional: verify these instead of sampling drafts   */
+  /* optional diagnostic outputs, NULL = not wanted */
+  int32_t* diag_draft_tokens;  /* [B, K] sampled (or given) draft tokens, -1 beyond window   */
+  float* diag_alpha;           /* [B, K] sum_v min(p_v, q_v)                                 */
+  float* diag_resid_mass;      /* [B, K] sum_v max(0, p_v - q_v)                             */
+  float* diag_lse;             /* [2, B, K] log-sum-exp of draft / target logits             */
+  float* diag_logits;          /* [2, B, K, V] scaled logits (draft rows first)              */
+  float* diag_conf_tok;        /* [B, K] pi(committed token) per slot, 0 where none          */
+  void* workspace;             /* device scratch, 256-byte aligned                           */
+  size_t workspace_bytes;
+  void* stream;                /* hipStream_t; NULL = the null stream                        */
+  void* ev_head_begin;         /* optional hipEvent_t recorded on `stream` right before ...  */
+  void* ev_head_end;           /* ... and right after the vocabulary-head kernel (profiling) */
+} fef_params;
+
+/* Bytes of device workspace a call with these sizes needs (depends on B, d, V, dtype,
+ * gemm_variant, K, block and on whether diag_alpha / diag_resid_mass are requested).
+ * Returns 0 if the arguments are invalid. */
+size_t fef_workspace_bytes(const fef_params* prm, int32_t K, int32_t block);
+
+/* One speculative round.  Argument order follows the statement of the problem:
+ *   h_draft   [B, K, d]  device, hidden state of window slot m in row m (draft forward)
+ *   h_target  [B, K, d]  device, prefix-conditioned target hidden state of slot m
+ *   W_vocab   [V, d]     device, row v = output embedding of token v (k contiguous)
+ *   K                    speculative window k
+ *   block                number of positions in the block
+ *   seed                 Philox key
+ *   out_tokens      [B, K]     device int32: committed token of slot m; -1 for slots after
+ *                              the corrected one and beyond the window
+ *   out_accept_len  [B]        device int32: accepted drafts a in [0, b]; committed
+ *                              positions are min(a+1, b)
+ *   out_remask      [B, block] device uint8: unresolved positions after the round
+ * Rows of h_* for slots beyond a sequence's window are read but ignored. */
+fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const void* h_target,
+                           const void* W_vocab, int32_t K, int32_t block, uint64_t seed,
+                           int32_t* out_tokens, int32_t* out_accept_len, uint8_t* out_remask);
+
+/* The head kernel AUTO would choose for these sizes (a fef_gemm_variant), or a negative
+ * fef_status.  Pure host function. */
+int32_t fef_select_gemm(const fef_params* prm, int32_t K);
+
+/* Philox4x32-10 word 0 -> uniform, evaluated on the host with the same code the kernels
+ * use; lets callers and tests reproduce a draw.  Pure host function. */
+float fef_uniform(uint64_t seed, uint32_t position, uint32_t step, uint32_t sequence,
+                  uint32_t stream);
+
+const char* fef_status_string(fef_status s);
+const char* fef_last_error(void);
+int32_t fef_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FEF_H */

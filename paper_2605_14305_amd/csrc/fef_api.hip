@@ -1,0 +1,214 @@
+// C ABI of the verify-step library: argument validation, workspace layout, kernel sequencing.
+// Everything is validated on the host before the first launch; nothing is allocated.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/fef.h"
+#include "fef_device.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+fef_status fail(fef_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+  int variant, tn, nT, nRC, all_slots;
+  long ldl;
+  size_t off_logits, off_partials, off_lse, off_xdraft, off_slot_pos, off_window, off_acc,
+      off_ptok, off_rmass, off_amass, total;
+};
+
+// Sizes only; no pointer checks.
+fef_status check_sizes(const fef_params* p, int32_t K, int32_t block) {
+  if (!p) return fail(FEF_ERR_INVALID_ARG, "params is NULL");
+  if (p->struct_size != sizeof(fef_params))
+    return fail(FEF_ERR_INVALID_ARG, "struct_size %u does not match this library's %zu",
+                p->struct_size, sizeof(fef_params));
+  if (p->B < 1 || p->d < 1 || p->V < 1)
+    return fail(FEF_ERR_INVALID_ARG, "B, d, V must be >= 1 (got %d, %d, %d)", p->B, p->d, p->V);
+  if (K < 1 || K > FEF_MAX_K || block < 1 || block > FEF_MAX_BLOCK || K > block)
+    return fail(FEF_ERR_INVALID_ARG, "need 1 <= K <= min(block, %d) and block <= %d (got K=%d, block=%d)",
+                FEF_MAX_K, FEF_MAX_BLOCK, K, block);
+  if (p->dtype != FEF_BF16 && p->dtype != FEF_F32)
+    return fail(FEF_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
+  if (!(p->temperature > 0.f) || !(p->temperature < 1e30f))
+    return fail(FEF_ERR_INVALID_ARG, "temperature must be a positive finite number");
+  if (p->dtype == FEF_BF16 && p->d % 64 != 0)
+    return fail(FEF_ERR_INVALID_ARG, "bf16 path needs d to be a multiple of 64 (got %d)", p->d);
+  if ((long)p->B * K > (1L << 24))
+    return fail(FEF_ERR_INVALID_ARG, "B*K = %ld exceeds 2^24 rows per call", (long)p->B * K);
+  if (p->lowconf_scope != 0 && p->lowconf_scope != 1)
+    return fail(FEF_ERR_INVALID_ARG, "lowconf_scope must be 0 or 1");
+  if (!p->conf && (p->pass_mask || p->lowconf_scope == 1))
+    return fail(FEF_ERR_INVALID_ARG, "conf may be NULL only with pass_mask NULL and lowconf_scope 0");
+  return FEF_OK;
+}
+
+fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
+  const long M = 2L * p->B * K;
+  int v = p->gemm_variant;
+  if (v == FEF_GEMM_AUTO) {
+    if (p->dtype == FEF_F32) v = FEF_GEMM_F32;
+    else v = fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d) ? FEF_GEMM_SKINNY : FEF_GEMM_TILED;
+  }
+  switch (v) {
+    case FEF_GEMM_SKINNY:
+      if (p->dtype != FEF_BF16 || !fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d))
+        return fail(FEF_ERR_UNSUPPORTED, "skinny head kernel needs bf16, 2*B*K <= 16 and d in {512, 3584, 4096}");
+      break;
+    case FEF_GEMM_TILED:
+      if (p->dtype != FEF_BF16) return fail(FEF_ERR_UNSUPPORTED, "tiled head kernel is bf16 only");
+      break;
+    case FEF_GEMM_F32:
+      if (p->dtype != FEF_F32) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel needs dtype f32");
+      if (M > 65535) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel serves at most 65535 rows");
+      break;
+    default:
+      return fail(FEF_ERR_INVALID_ARG, "unknown gemm_variant %d", v);
+  }
+  *variant = v;
+  return FEF_OK;
+}
+
+fef_status make_layout(const fef_params* p, int32_t K, int32_t block, Layout* L) {
+  fef_status s = check_sizes(p, K, block);
+  if (s != FEF_OK) return s;
+  s = select_variant(p, K, &L->variant);
+  if (s != FEF_OK) return s;
+  const size_t BK = (size_t)p->B * K, M = 2 * BK;
+  L->tn = L->variant == FEF_GEMM_SKINNY ? fef::kSkinnyTn : fef::kTiledTn;
+  L->nT = (p->V + L->tn - 1) / L->tn;
+  L->nRC = (p->V + fef::kResidChunk - 1) / fef::kResidChunk;
+  L->ldl = (long)align_up((size_t)p->V, 64);
+  L->all_slots = (p->diag_alpha || p->diag_resid_mass) ? 1 : 0;
+  const size_t nslots = L->all_slots ? BK : (size_t)p->B;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+  L->off_logits = take(M * (size_t)L->ldl * sizeof(float));
+  L->off_partials = take(M * (size_t)L->nT * sizeof(float2));
+  L->off_lse = take(M * sizeof(float));
+  L->off_xdraft = take(BK * sizeof(int32_t));
+  L->off_slot_pos = take(BK * sizeof(int32_t));
+  L->off_window = take((size_t)p->B * sizeof(int32_t));
+  L->off_acc = take((size_t)p->B * sizeof(int32_t));
+  L->off_ptok = take(BK * sizeof(float));
+  L->off_rmass = take(nslots * (size_t)L->nRC * sizeof(float));
+  L->off_amass = take(L->all_slots ? nslots * (size_t)L->nRC * sizeof(float) : 0);
+  L->total = o;
+  return FEF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t fef_workspace_bytes(const fef_params* prm, int32_t K, int32_t block) {
+  Layout L;
+  if (make_layout(prm, K, block, &L) != FEF_OK) return 0;
+  return L.total;
+}
+
+int32_t fef_select_gemm(const fef_params* prm, int32_t K) {
+  fef_status s = check_sizes(prm, K, K > 0 ? (K > FEF_MAX_BLOCK ? FEF_MAX_BLOCK : K) : 1);
+  if (s != FEF_OK) return s;
+  int v = 0;
+  s = select_variant(prm, K, &v);
+  return s != FEF_OK ? (int32_t)s : v;
+}
+
+fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const void* h_target,
+                           const void* W_vocab, int32_t K, int32_t block, uint64_t seed,
+                           int32_t* out_tokens, int32_t* out_accept_len, uint8_t* out_remask) {
+  Layout L;
+  fef_status s = make_layout(prm, K, block, &L);
+  if (s != FEF_OK) return s;
+  if (!h_draft || !h_target || !W_vocab)
+    return fail(FEF_ERR_INVALID_ARG, "h_draft, h_target and W_vocab must not be NULL");
+  if (!out_tokens || !out_accept_len || !out_remask)
+    return fail(FEF_ERR_INVALID_ARG, "out_tokens, out_accept_len and out_remask must not be NULL");
+  if (((uintptr_t)h_draft | (uintptr_t)h_target | (uintptr_t)W_vocab) & 15)
+    return fail(FEF_ERR_INVALID_ARG, "h_draft, h_target and W_vocab must be 16-byte aligned");
+  if (!prm->workspace) return fail(FEF_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", L.total);
+  if ((uintptr_t)prm->workspace & 255) return fail(FEF_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (prm->workspace_bytes < L.total)
+    return fail(FEF_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", prm->workspace_bytes, L.total);
+
+  char* ws = (char*)prm->workspace;
+  hipStream_t stream = (hipStream_t)prm->stream;
+
+  fef::HeadArgs h;
+  h.h_draft = h_draft; h.h_target = h_target; h.W = W_vocab;
+  h.BK = prm->B * K; h.d = prm->d; h.V = prm->V;
+  h.inv_tau = 1.0f / prm->temperature;
+  h.logits = (float*)(ws + L.off_logits); h.ldl = L.ldl;
+  h.partials = (float2*)(ws + L.off_partials); h.nT = L.nT;
+  h.stream = stream;
+  hipError_t e;
+  if (prm->ev_head_begin && (e = hipEventRecord((hipEvent_t)prm->ev_head_begin, stream)) != hipSuccess)
+    return fail(FEF_ERR_HIP, "hipEventRecord: %s", hipGetErrorString(e));
+  switch (L.variant) {
+    case FEF_GEMM_SKINNY: e = fef::launch_head_skinny(h); break;
+    case FEF_GEMM_TILED: e = fef::launch_head_tiled(h); break;
+    default: e = fef::launch_head_f32(h); break;
+  }
+  if (e != hipSuccess) return fail(FEF_ERR_HIP, "head kernel launch: %s", hipGetErrorString(e));
+  if (prm->ev_head_end && (e = hipEventRecord((hipEvent_t)prm->ev_head_end, stream)) != hipSuccess)
+    return fail(FEF_ERR_HIP, "hipEventRecord: %s", hipGetErrorString(e));
+
+  fef::VerifyArgs v;
+  memset(&v, 0, sizeof v);
+  v.B = prm->B; v.K = K; v.block = block; v.V = prm->V;
+  v.ldl = L.ldl; v.logits = h.logits; v.partials = h.partials; v.nT = L.nT; v.tn = L.tn;
+  v.seed = seed; v.step = prm->step; v.seq_base = prm->seq_base; v.pos_base = prm->pos_base;
+  v.n_rm = prm->n_rm; v.final_pass = prm->final_pass; v.lowconf_scope = prm->lowconf_scope;
+  v.mask_in = prm->mask_in; v.pass_mask = prm->pass_mask; v.conf = prm->conf;
+  v.draft_tokens_in = prm->draft_tokens;
+  v.lse = (float*)(ws + L.off_lse);
+  v.xdraft = (int32_t*)(ws + L.off_xdraft);
+  v.slot_pos = (int32_t*)(ws + L.off_slot_pos);
+  v.window = (int32_t*)(ws + L.off_window);
+  v.accept_len_ws = (int32_t*)(ws + L.off_acc);
+  v.ptok = (float*)(ws + L.off_ptok);
+  v.rmass = (float*)(ws + L.off_rmass);
+  v.amass = (float*)(ws + L.off_amass);
+  v.nRC = L.nRC; v.all_slots = L.all_slots;
+  v.out_tokens = out_tokens; v.out_accept_len = out_accept_len; v.out_remask = out_remask;
+  v.diag_draft_tokens = prm->diag_draft_tokens; v.diag_alpha = prm->diag_alpha;
+  v.diag_resid_mass = prm->diag_resid_mass; v.diag_lse = prm->diag_lse;
+  v.diag_logits = prm->diag_logits; v.diag_conf_tok = prm->diag_conf_tok;
+  v.stream = stream;
+  e = fef::launch_verify(v);
+  if (e != hipSuccess) return fail(FEF_ERR_HIP, "verify kernel launch: %s", hipGetErrorString(e));
+  return FEF_OK;
+}
+
+float fef_uniform(uint64_t seed, uint32_t position, uint32_t step, uint32_t sequence, uint32_t stream) {
+  return fef::philox_uniform(seed, position, step, sequence, stream);
+}
+
+const char* fef_status_string(fef_status s) {
+  switch (s) {
+    case FEF_OK: return "ok";
+    case FEF_ERR_INVALID_ARG: return "invalid argument";
+    case FEF_ERR_UNSUPPORTED: return "unsupported configuration";
+    case FEF_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case FEF_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* fef_last_error(void) { return g_err; }
+
+int32_t fef_abi_version(void) { return FEF_ABI_VERSION; }
+
+}  // extern "C"

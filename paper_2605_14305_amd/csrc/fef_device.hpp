@@ -1,0 +1,108 @@
+// Shared declarations of the verify-step library: kernel launchers, the Philox generator
+// and wavefront / workgroup scan primitives.  gfx950 only (64-wide wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fef {
+
+constexpr int kWave = 64;
+constexpr int kMaxBlock = 4096;  // positions per block (FEF_MAX_BLOCK)
+constexpr int kMaxK = 64;        // window (FEF_MAX_K): one ballot covers a window
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  key = (seed lo, seed hi); counter = (position, step,
+// sequence, stream); word 0 of the output is used.
+// ---------------------------------------------------------------------------------------------
+constexpr uint32_t kStreamDraft = 0, kStreamAccept = 1, kStreamResidual = 2;
+
+__host__ __device__ inline uint32_t philox_word0(uint64_t seed, uint32_t c0, uint32_t c1,
+                                                 uint32_t c2, uint32_t c3) {
+  uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+  }
+  return c0;
+}
+
+// Top 23 bits -> u = (n + 1/2) 2^-23 in (0,1); every value is exact in fp32.
+__host__ __device__ inline float word_to_uniform(uint32_t w) {
+  return ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;
+}
+
+__host__ __device__ inline float philox_uniform(uint64_t seed, uint32_t position, uint32_t step,
+                                                uint32_t sequence, uint32_t stream) {
+  return word_to_uniform(philox_word0(seed, position, step, sequence, stream));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Arguments of the vocabulary-head kernels: L[r, v] = inv_tau * sum_k H[r, k] W[v, k] for the
+// 2*BK rows (draft rows first), written once as fp32, plus per (row, vocab tile of `tn`)
+// partials (max, sum exp(L - max)) for the log-sum-exp.
+// ---------------------------------------------------------------------------------------------
+struct HeadArgs {
+  const void* h_draft;   // [BK, d]
+  const void* h_target;  // [BK, d]
+  const void* W;         // [V, d]
+  int BK, d, V;
+  float inv_tau;
+  float* logits;         // [2*BK, ldl]
+  long ldl;
+  float2* partials;      // [2*BK, nT]
+  int nT;                // ceil(V / tn)
+  hipStream_t stream;
+};
+
+constexpr int kSkinnyTn = 16;  // partial-tile width written by the skinny kernel
+constexpr int kTiledTn = 64;   // ... by the tiled and f32 kernels
+
+bool skinny_supports(int M, int d);
+hipError_t launch_head_skinny(const HeadArgs& a);
+hipError_t launch_head_tiled(const HeadArgs& a);
+hipError_t launch_head_f32(const HeadArgs& a);
+
+// ---------------------------------------------------------------------------------------------
+// Arguments of the sampling / verification kernels that follow the head.
+// ---------------------------------------------------------------------------------------------
+constexpr int kResidChunk = 256;  // vocabulary entries per residual-mass chunk
+
+struct VerifyArgs {
+  int B, K, block, V;
+  long ldl;
+  const float* logits;      // [2*B*K, ldl]
+  const float2* partials;   // [2*B*K, nT]
+  int nT, tn;
+  uint64_t seed;
+  uint32_t step, seq_base, pos_base;
+  int n_rm, final_pass, lowconf_scope;
+  const uint8_t* mask_in;
+  uint8_t* pass_mask;
+  float* conf;
+  const int32_t* draft_tokens_in;
+  // workspace
+  float* lse;               // [2*B*K]
+  int32_t* xdraft;          // [B*K]
+  int32_t* slot_pos;        // [B*K]
+  int32_t* window;          // [B]
+  int32_t* accept_len_ws;   // [B]
+  float* ptok;              // [B*K] pi(x~)
+  float* rmass;             // [nslots, nRC] residual mass per chunk
+  float* amass;             // [nslots, nRC] overlap mass per chunk (all_slots only)
+  int nRC;                  // ceil(V / kResidChunk)
+  int all_slots;            // 1: masses for every slot (diagnostics), 0: rejected slot only
+  // outputs
+  int32_t* out_tokens; int32_t* out_accept_len; uint8_t* out_remask;
+  int32_t* diag_draft_tokens; float* diag_alpha; float* diag_resid_mass; float* diag_lse;
+  float* diag_logits; float* diag_conf_tok;
+  hipStream_t stream;
+};
+
+hipError_t launch_verify(const VerifyArgs& a);
+
+}  // namespace fef

@@ -1,0 +1,300 @@
+// Vocabulary-head kernels: L[r, v] = inv_tau * sum_k H[r, k] W[v, k] for the draft rows
+// followed by the target rows (the two laws of Algorithm 2, "Compute draft laws" and "Compute
+// target laws", share one pass over W because the paper uses one network for both), fp32
+// logits written once, and per (row, vocabulary tile) partials (max, sum exp(L - max)) from
+// which the row's log-sum-exp is merged later.
+//
+//   head_skinny_kernel  M = 2*B*K <= 16.  HBM-bound: W (about 1 GB) is streamed exactly once.
+//                       Eight wavefronts split k; each keeps its slice of H in registers as
+//                       the MFMA B operand for the whole kernel, streams its 1 KB slice of
+//                       sixteen W rows straight into the MFMA A operand registers one tile
+//                       ahead, and the eight partial 16x16 tiles are summed through LDS.
+//   head_tiled_kernel   any M.  128x128x64 LDS-tiled MFMA GEMM, XCD-aware tile order so the
+//                       workgroups that share a W tile run on the same L2.
+//   head_f32_kernel     fp32 inputs, plain FMA; tiny instances only.
+#include <math.h>
+
+#include "fef_device.hpp"
+
+namespace fef {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Workgroup barrier that waits for this wavefront's LDS traffic only.  __syncthreads() would
+// also drain the vector-memory counter and with it the W tiles prefetched for later steps.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+__device__ inline const __bf16* h_row(const HeadArgs& a, int r) {
+  return r < a.BK ? (const __bf16*)a.h_draft + (size_t)r * a.d
+                  : (const __bf16*)a.h_target + (size_t)(r - a.BK) * a.d;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Skinny kernel.  KS = MFMA k-steps (32 wide) per wavefront; d = 8 * KS * 32.
+//
+// v_mfma_f32_16x16x32_bf16 operand layout (lane l, i = l % 16, g = l / 16):
+//   A (16 x 32): lane holds A[i][8g .. 8g+7]        -> W tile row i, 16 contiguous bytes
+//   B (32 x 16): lane holds B[8g .. 8g+7][i]        -> H row i, the same k range
+//   D (16 x 16): lane holds D[4g + r][i], r = 0..3  -> logits of 4 consecutive tokens, row i
+// ---------------------------------------------------------------------------------------------
+constexpr int kSkinnyWaves = 8;
+constexpr int kSkinnyThreads = kSkinnyWaves * kWave;
+
+template <int KS>
+__global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a, int tiles_total) {
+  __shared__ floatx4 red[2][kSkinnyWaves][kWave];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, g = lane >> 4;
+  const int M = 2 * a.BK;
+  const int kofs = wave * (KS * 32) + g * 8;  // first k of this lane; k-step s adds 32 s
+
+  bf16x8 hreg[KS];
+  {
+    const bool live = i16 < M;
+    const __bf16* hp = h_row(a, live ? i16 : 0) + kofs;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      bf16x8 v = *reinterpret_cast<const bf16x8*>(hp + 32 * s);
+      if (!live) v = bf16x8{};
+      hreg[s] = v;
+    }
+  }
+
+  const int t0 = (int)((long)blockIdx.x * tiles_total / gridDim.x);
+  const int t1 = (int)((long)(blockIdx.x + 1) * tiles_total / gridDim.x);
+  const __bf16* Wl = (const __bf16*)a.W + kofs;
+
+  auto load_tile = [&](int t, bf16x8(&buf)[KS]) {
+    const int v = min(t * 16 + i16, a.V - 1);  // rows past V re-read the last row, masked later
+    const __bf16* wp = Wl + (size_t)v * a.d;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) buf[s] = *reinterpret_cast<const bf16x8*>(wp + 32 * s);
+  };
+
+  auto compute_tile = [&](int t, const bf16x8(&buf)[KS], int par) {
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[s], hreg[s], acc, 0, 0, 0);
+    red[par][wave][lane] = acc;
+    lds_barrier();
+    if (tid < 256) {
+      // thread -> (row m, token vl) of the 16x16 tile; sum the eight k-slices in wave order
+      const int m = tid >> 4, vl = tid & 15;
+      const int src = m + 16 * (vl >> 2), comp = vl & 3;
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < kSkinnyWaves; ++w) sum += red[par][w][src][comp];
+      const float logit = sum * a.inv_tau;
+      const int v = t * 16 + vl;
+      const bool valid = v < a.V && m < M;
+      if (valid) a.logits[(size_t)m * a.ldl + v] = logit;
+      float mx = valid ? logit : -INFINITY;
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      float e = valid ? __expf(logit - mx) : 0.f;
+#pragma unroll
+      for (int off = 8; off >= 1; off >>= 1) e += __shfl_xor(e, off, 64);
+      if (vl == 0 && m < M) a.partials[(size_t)m * a.nT + t] = make_float2(mx, e);
+    }
+  };
+
+  bf16x8 buf0[KS], buf1[KS];
+  if (t0 < t1) load_tile(t0, buf0);
+  for (int t = t0; t < t1; t += 2) {
+    if (t + 1 < t1) load_tile(t + 1, buf1);
+    compute_tile(t, buf0, 0);
+    if (t + 1 < t1) {
+      if (t + 2 < t1) load_tile(t + 2, buf0);
+      compute_tile(t + 1, buf1, 1);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tiled kernel: workgroup tile 128 (rows of H) x 128 (tokens) x 64 (k), four wavefronts in a
+// 2 x 2 grid, each 64 x 64 as 2 x 2 v_mfma_f32_32x32x16_bf16 tiles.
+//
+// 32x32x16 operand layout (lane l, j = l % 32, h = l / 32):
+//   A (32 x 16): lane holds A[j][8h .. 8h+7]     -> H row j
+//   B (16 x 32): lane holds B[8h .. 8h+7][j]     -> W row (token) j
+//   D (32 x 32): lane holds D[8 (r/4) + 4h + r%4][j], r = 0..15
+// LDS tiles are [128 rows][64 k] bf16 = 128 B per row; the eight 16-byte chunks of a row are
+// stored at chunk ^ (row & 7) so the 16-byte reads of one k-chunk over 32 rows spread over all
+// banks.
+// ---------------------------------------------------------------------------------------------
+constexpr int TM = 128, TN = 128, TK = 64;
+constexpr int kTiledThreads = 256;
+
+__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
+
+__global__ __launch_bounds__(kTiledThreads) void head_tiled_kernel(HeadArgs a, int m_tiles, int n_tiles) {
+  __shared__ bf16x8 As[TM * 8];
+  __shared__ bf16x8 Bs[TN * 8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int j32 = lane & 31, h = lane >> 5;
+  const int M = 2 * a.BK;
+
+  // XCD-aware order: workgroup ids round-robin over the 8 XCDs, so ids with the same id % 8
+  // share an L2.  Within one XCD, consecutive workgroups walk the row tiles of one token tile.
+  const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  const int nt = xcd + 8 * (seq / m_tiles), mt = seq % m_tiles;
+  if (nt >= n_tiles) return;
+  const int m0 = mt * TM, n0 = nt * TN;
+
+  // global -> register staging: thread loads chunk (tid % 8) of rows tid/8 + 32 j, j = 0..3
+  const int lc = tid & 7, lr = tid >> 3;
+  const __bf16* ap[4];
+  const __bf16* bp[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = min(m0 + lr + 32 * j, M - 1);
+    const int v = min(n0 + lr + 32 * j, a.V - 1);
+    ap[j] = h_row(a, r) + lc * 8;
+    bp[j] = (const __bf16*)a.W + (size_t)v * a.d + lc * 8;
+  }
+  bf16x8 ra[4], rb[4];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      ra[j] = *reinterpret_cast<const bf16x8*>(ap[j] + k0);
+      rb[j] = *reinterpret_cast<const bf16x8*>(bp[j] + k0);
+    }
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = floatx16{};
+
+  gload(0);
+  for (int k0 = 0; k0 < a.d; k0 += TK) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      As[swz(lr + 32 * j, lc)] = ra[j];
+      Bs[swz(lr + 32 * j, lc)] = rb[j];
+    }
+    lds_barrier();
+    if (k0 + TK < a.d) gload(k0 + TK);
+#pragma unroll
+    for (int ks = 0; ks < TK / 16; ++ks) {
+      bf16x8 af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = As[swz(wm * 64 + i * 32 + j32, ks * 2 + h)];
+        bf[i] = Bs[swz(wn * 64 + i * 32 + j32, ks * 2 + h)];
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    lds_barrier();
+  }
+
+  // epilogue: scale, store, per-row (max, sum exp) over this wavefront's 64 tokens
+  const int vbase = n0 + wn * 64;
+  const int ptile = vbase / kTiledTn;
+  const bool tile_live = vbase < a.V;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+      const int v0 = vbase + j32, v1 = v0 + 32;
+      const float l0 = acc[i][0][r] * a.inv_tau, l1 = acc[i][1][r] * a.inv_tau;
+      const bool ok0 = m < M && v0 < a.V, ok1 = m < M && v1 < a.V;
+      if (ok0) a.logits[(size_t)m * a.ldl + v0] = l0;
+      if (ok1) a.logits[(size_t)m * a.ldl + v1] = l1;
+      float mx = fmaxf(ok0 ? l0 : -INFINITY, ok1 ? l1 : -INFINITY);
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      float e = (ok0 ? __expf(l0 - mx) : 0.f) + (ok1 ? __expf(l1 - mx) : 0.f);
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) e += __shfl_xor(e, off, 64);
+      if (j32 == 0 && m < M && tile_live) a.partials[(size_t)m * a.nT + ptile] = make_float2(mx, e);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 kernel: one wavefront per (row, 64-token tile), lane = token, sequential FMA over k.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWave) void head_f32_kernel(HeadArgs a) {
+  const int lane = threadIdx.x;
+  const int t = blockIdx.x, r = blockIdx.y;
+  const int v = t * kTiledTn + lane;
+  const bool valid = v < a.V;
+  const float* hp = r < a.BK ? (const float*)a.h_draft + (size_t)r * a.d
+                             : (const float*)a.h_target + (size_t)(r - a.BK) * a.d;
+  const float* wp = (const float*)a.W + (size_t)(valid ? v : a.V - 1) * a.d;
+  float acc = 0.f;
+  for (int k = 0; k < a.d; ++k) acc = fmaf(hp[k], wp[k], acc);
+  const float logit = acc * a.inv_tau;
+  if (valid) a.logits[(size_t)r * a.ldl + v] = logit;
+  float mx = valid ? logit : -INFINITY;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+  float e = valid ? expf(logit - mx) : 0.f;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) e += __shfl_xor(e, off, 64);
+  if (lane == 0) a.partials[(size_t)r * a.nT + t] = make_float2(mx, e);
+}
+
+int compute_units() {
+  static int cached = 0;
+  if (!cached) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cached = n;
+    else
+      cached = 256;
+  }
+  return cached;
+}
+
+}  // namespace
+
+bool skinny_supports(int M, int d) { return M <= 16 && (d == 512 || d == 3584 || d == 4096); }
+
+hipError_t launch_head_skinny(const HeadArgs& a) {
+  const int tiles = (a.V + 15) / 16;
+  const int grid = tiles < compute_units() ? tiles : compute_units();
+  switch (a.d) {
+    case 512:
+      hipLaunchKernelGGL(head_skinny_kernel<2>, dim3(grid), dim3(kSkinnyThreads), 0, a.stream, a, tiles);
+      break;
+    case 3584:
+      hipLaunchKernelGGL(head_skinny_kernel<14>, dim3(grid), dim3(kSkinnyThreads), 0, a.stream, a, tiles);
+      break;
+    case 4096:
+      hipLaunchKernelGGL(head_skinny_kernel<16>, dim3(grid), dim3(kSkinnyThreads), 0, a.stream, a, tiles);
+      break;
+    default:
+      return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_head_tiled(const HeadArgs& a) {
+  const int M = 2 * a.BK;
+  const int m_tiles = (M + TM - 1) / TM, n_tiles = (a.V + TN - 1) / TN;
+  const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
+  hipLaunchKernelGGL(head_tiled_kernel, dim3((unsigned)grid), dim3(kTiledThreads), 0, a.stream, a,
+                     m_tiles, n_tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_f32(const HeadArgs& a) {
+  hipLaunchKernelGGL(head_f32_kernel, dim3(a.nT, 2 * a.BK), dim3(kWave), 0, a.stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace fef

@@ -1,0 +1,483 @@
+// Sampling and verification kernels that follow the vocabulary head (Algorithm 2 of the
+// paper, lines "Sample draft tokens" to "break", and the LowConf re-corruption):
+//
+//   row_lse_draft_kernel   one workgroup per logits row: merge the per-tile (max, sum exp)
+//                          partials into the row's log-sum-exp; draft rows also locate their
+//                          window slot and draw x~ ~ rho by a two-level inverse CDF.
+//   accept_resid_kernel    per sequence: accept tests u <= min{1, pi(x~)/rho(x~)}, first
+//                          rejection by ballot; then per 256-token chunk the residual mass
+//                          sum [pi - rho]_+ (and the overlap mass sum min{pi, rho}) of the
+//                          rejected slot.
+//   finalize_kernel        per sequence: inverse CDF over the residual chunks and inside the
+//                          selected chunk, commit tokens and confidences, update the block
+//                          mask and apply LowConf.
+//
+// Every floating-point reduction uses a fixed tree (no atomics), so results are reproducible
+// bit for bit.
+#include <limits.h>
+#include <math.h>
+
+#include "fef_device.hpp"
+
+namespace fef {
+namespace {
+
+constexpr int NT = 256;          // threads per workgroup of every kernel in this file
+constexpr int NW = NT / kWave;   // wavefronts per workgroup
+
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+__device__ inline float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+  return x;
+}
+__device__ inline int wave_min_int(int x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x = min(x, __shfl_xor(x, off, 64));
+  return x;
+}
+__device__ inline int wave_max_int(int x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x = max(x, __shfl_xor(x, off, 64));
+  return x;
+}
+
+struct BlockTmp {
+  float f[NW];
+  int i[NW];
+  float bcast_f;
+  int bcast_i;
+};
+
+__device__ inline float block_sum(float x, BlockTmp& t) {
+  x = wave_sum(x);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) t.f[threadIdx.x >> 6] = x;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) s += t.f[w];
+  return s;
+}
+__device__ inline float block_max(float x, BlockTmp& t) {
+  x = wave_max(x);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) t.f[threadIdx.x >> 6] = x;
+  __syncthreads();
+  float s = t.f[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) s = fmaxf(s, t.f[w]);
+  return s;
+}
+__device__ inline int block_min_int(int x, BlockTmp& t) {
+  x = wave_min_int(x);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) t.i[threadIdx.x >> 6] = x;
+  __syncthreads();
+  int s = t.i[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) s = min(s, t.i[w]);
+  return s;
+}
+__device__ inline int block_max_int(int x, BlockTmp& t) {
+  x = wave_max_int(x);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) t.i[threadIdx.x >> 6] = x;
+  __syncthreads();
+  int s = t.i[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) s = max(s, t.i[w]);
+  return s;
+}
+
+// Exclusive prefix sum of one value per thread in thread order; `total` gets the sum.
+__device__ inline float block_exclusive_scan(float x, BlockTmp& t, float& total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float inc = x;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const float y = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += y;
+  }
+  float exc = __shfl_up(inc, 1, 64);
+  if (lane == 0) exc = 0.f;
+  __syncthreads();
+  if (lane == 63) t.f[w] = inc;
+  __syncthreads();
+  float base = 0.f, tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    if (i == w) base = tot;
+    tot += t.f[i];
+  }
+  total = tot;
+  return base + exc;
+}
+
+struct Found {
+  int idx;       // first index whose inclusive prefix sum reaches the target
+  float before;  // prefix sum of everything before idx
+  float total;   // sum of all masses
+};
+
+// min{i in [0,n) : sum_{j<=i} mass(j) >= target} over non-negative masses, ascending i.
+// Thread t owns the contiguous segment [t*per, (t+1)*per).  If rounding leaves every prefix
+// below the target, the last index with positive mass is returned (index 0 if there is none).
+template <class F>
+__device__ inline Found block_find_first(int n, F mass, float target, BlockTmp& t) {
+  const int per = (n + NT - 1) / NT;
+  const int begin = min(n, (int)threadIdx.x * per), end = min(n, begin + per);
+  float local = 0.f;
+  for (int i = begin; i < end; ++i) local += mass(i);
+  float total;
+  const float exc = block_exclusive_scan(local, t, total);
+  float run = exc, before = 0.f, before_pos = 0.f;
+  int cand = INT_MAX, last_pos = -1;
+  for (int i = begin; i < end; ++i) {
+    const float mi = mass(i);
+    const float nxt = run + mi;
+    if (mi > 0.f) { last_pos = i; before_pos = run; }
+    if (cand == INT_MAX && nxt >= target) { cand = i; before = run; }
+    run = nxt;
+  }
+  int win = block_min_int(cand, t);
+  bool mine = cand != INT_MAX && cand == win;
+  if (win == INT_MAX) {  // target not reached: fall back to the last positive mass
+    const int lp = block_max_int(last_pos, t);
+    if (lp < 0) { win = 0; mine = threadIdx.x == 0; before = 0.f; }
+    else { win = lp; mine = last_pos == lp; before = before_pos; }
+  }
+  __syncthreads();
+  if (mine) t.bcast_f = before;
+  __syncthreads();
+  Found f;
+  f.idx = win;
+  f.before = t.bcast_f;
+  f.total = total;
+  return f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 1: per-row log-sum-exp, window slot, draft sample.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
+  __shared__ BlockTmp tmp;
+  __shared__ int s_pos, s_cnt;
+  const int tid = threadIdx.x;
+  const int BK = a.B * a.K;
+  const int r = blockIdx.x;
+  const bool is_draft = r < BK;
+  const int s = is_draft ? r : r - BK;
+  const int b = s / a.K, m = s % a.K;
+
+  // log-sum-exp of the row from the head kernel's per-tile partials
+  const float2* P = a.partials + (size_t)r * a.nT;
+  float mx = -INFINITY;
+  for (int t = tid; t < a.nT; t += NT) mx = fmaxf(mx, P[t].x);
+  mx = block_max(mx, tmp);
+  float sm = 0.f;
+  for (int t = tid; t < a.nT; t += NT) {
+    const float2 p = P[t];
+    sm += p.y * expf(p.x - mx);
+  }
+  sm = block_sum(sm, tmp);
+  const float lse = mx + logf(sm);
+  if (tid == 0) {
+    a.lse[r] = lse;
+    if (a.diag_lse) a.diag_lse[r] = lse;
+  }
+  if (!is_draft) return;
+
+  // window slot m = (m+1)-th unresolved position of the block, ascending
+  if (tid < kWave) {
+    int cnt = 0, pos = -1;
+    for (int base = 0; base < a.block; base += kWave) {
+      const int i = base + tid;
+      const bool bit = i < a.block && (a.mask_in ? a.mask_in[(size_t)b * a.block + i] != 0 : true);
+      const unsigned long long bal = __ballot(bit);
+      const int rank = cnt + __popcll(bal & ((1ull << tid) - 1ull));
+      if (bit && rank == m) pos = i;
+      cnt += __popcll(bal);
+    }
+    pos = wave_max_int(pos);
+    if (tid == 0) { s_pos = pos; s_cnt = cnt; }
+  }
+  __syncthreads();
+  const int pos = s_pos;
+  const int window = min(a.K, s_cnt);
+  if (tid == 0) {
+    a.slot_pos[s] = pos;
+    if (m == 0) a.window[b] = window;
+  }
+  if (m >= window) {
+    if (tid == 0) {
+      a.xdraft[s] = -1;
+      if (a.diag_draft_tokens) a.diag_draft_tokens[s] = -1;
+    }
+    return;
+  }
+
+  int x;
+  if (a.draft_tokens_in) {
+    x = min(max(a.draft_tokens_in[s], 0), a.V - 1);  // keep the gathers in bounds
+  } else {
+    // x~ = min{v : sum_{w<=v} rho_w >= u}: first over vocabulary tiles, then inside the tile
+    const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)pos, a.step,
+                                   a.seq_base + (uint32_t)b, kStreamDraft);
+    const Found tile = block_find_first(
+        a.nT, [&](int t) { const float2 p = P[t]; return p.y * expf(p.x - lse); }, u, tmp);
+    const float* L = a.logits + (size_t)r * a.ldl;
+    const int v0 = tile.idx * a.tn;
+    const int nv = min(a.tn, a.V - v0);
+    const Found in = block_find_first(
+        nv, [&](int i) { return expf(L[v0 + i] - lse); }, u - tile.before, tmp);
+    x = v0 + in.idx;
+  }
+  if (tid == 0) {
+    a.xdraft[s] = x;
+    if (a.diag_draft_tokens) a.diag_draft_tokens[s] = x;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 2: accept tests, first rejection, residual / overlap mass per chunk.
+// grid = (nslots, ceil(nRC / NW)); nslots = B (rejected slot only) or B*K (every slot).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void accept_resid_kernel(VerifyArgs a) {
+  __shared__ int s_a;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int BK = a.B * a.K;
+  const int y = blockIdx.x;            // slot (or sequence) index
+  const int cg = blockIdx.y;           // chunk group
+  const int b = a.all_slots ? y / a.K : y;
+  const int window = a.window[b];
+
+  if (wave == 0) {
+    bool rejected = false;
+    float pt = 0.f;
+    if (lane < window) {
+      const int s = b * a.K + lane;
+      const int x = a.xdraft[s];
+      const float lq = a.logits[(size_t)s * a.ldl + x] - a.lse[s];
+      const float lp = a.logits[(size_t)(BK + s) * a.ldl + x] - a.lse[BK + s];
+      const float ratio = fminf(1.f, expf(lp - lq));
+      const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
+                                     a.seq_base + (uint32_t)b, kStreamAccept);
+      rejected = !(u <= ratio);
+      pt = expf(lp);
+      if (cg == 0 && (!a.all_slots || y % a.K == 0)) a.ptok[s] = pt;
+    }
+    const unsigned long long rej = __ballot(rejected);
+    const int acc_len = rej ? __ffsll((long long)rej) - 1 : window;
+    if (lane == 0) {
+      s_a = acc_len;
+      if (cg == 0 && (!a.all_slots || y % a.K == 0)) a.accept_len_ws[b] = acc_len;
+    }
+  }
+  __syncthreads();
+  const int acc_len = s_a;
+  const int m = a.all_slots ? y % a.K : acc_len;
+  if (m >= window) return;  // nothing rejected (or slot beyond the window): no masses needed
+
+  const int c = cg * NW + wave;
+  if (c >= a.nRC) return;
+  const int s = b * a.K + m;
+  const float* Lq = a.logits + (size_t)s * a.ldl;
+  const float* Lp = a.logits + (size_t)(BK + s) * a.ldl;
+  const float lse_q = a.lse[s], lse_p = a.lse[BK + s];
+  const int v = c * kResidChunk + lane * 4;
+  float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f), p4 = q4;
+  if (v + 3 < a.V) {
+    q4 = *reinterpret_cast<const float4*>(Lq + v);
+    p4 = *reinterpret_cast<const float4*>(Lp + v);
+  } else {
+    float* qq = reinterpret_cast<float*>(&q4);
+    float* pp = reinterpret_cast<float*>(&p4);
+    for (int j = 0; j < 4; ++j)
+      if (v + j < a.V) { qq[j] = Lq[v + j]; pp[j] = Lp[v + j]; }
+  }
+  const float qv[4] = {q4.x, q4.y, q4.z, q4.w}, pv[4] = {p4.x, p4.y, p4.z, p4.w};
+  float rs = 0.f, as = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (v + j < a.V) {
+      const float q = expf(qv[j] - lse_q), p = expf(pv[j] - lse_p);
+      rs += fmaxf(p - q, 0.f);
+      as += fminf(p, q);
+    }
+  }
+  rs = wave_sum(rs);
+  if (a.all_slots) as = wave_sum(as);
+  if (lane == 0) {
+    a.rmass[(size_t)y * a.nRC + c] = rs;
+    if (a.all_slots) a.amass[(size_t)y * a.nRC + c] = as;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 3: residual sample, commit, mask update, LowConf.  One workgroup per sequence.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
+  __shared__ BlockTmp tmp;
+  __shared__ float s_conf[kMaxBlock];
+  __shared__ uint8_t s_mask[kMaxBlock], s_cand[kMaxBlock];
+  const int tid = threadIdx.x;
+  const int b = blockIdx.x;
+  const int BK = a.B * a.K;
+  const int window = a.window[b];
+  const int acc_len = a.accept_len_ws[b];
+
+  // diagnostics: overlap and residual mass of every slot
+  if (a.all_slots) {
+    for (int m = 0; m < a.K; ++m) {
+      float al = 0.f, rm = 0.f;
+      if (m < window) {
+        const size_t base = (size_t)(b * a.K + m) * a.nRC;
+        for (int c = tid; c < a.nRC; c += NT) { al += a.amass[base + c]; rm += a.rmass[base + c]; }
+        al = block_sum(al, tmp);
+        rm = block_sum(rm, tmp);
+      }
+      if (tid == 0) {
+        if (a.diag_alpha) a.diag_alpha[b * a.K + m] = al;
+        if (a.diag_resid_mass) a.diag_resid_mass[b * a.K + m] = rm;
+      }
+    }
+  }
+
+  // corrected token at the first rejection
+  int z = -1;
+  float z_conf = 0.f;
+  if (acc_len < window) {
+    const int s = b * a.K + acc_len;
+    const float* Lq = a.logits + (size_t)s * a.ldl;
+    const float* Lp = a.logits + (size_t)(BK + s) * a.ldl;
+    const float lse_q = a.lse[s], lse_p = a.lse[BK + s];
+    const float* rm = a.rmass + (size_t)(a.all_slots ? s : b) * a.nRC;
+    const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
+                                   a.seq_base + (uint32_t)b, kStreamResidual);
+    float Z = 0.f;
+    {
+      const int per = (a.nRC + NT - 1) / NT;
+      const int begin = min(a.nRC, tid * per), end = min(a.nRC, begin + per);
+      float local = 0.f;
+      for (int c = begin; c < end; ++c) local += rm[c];
+      block_exclusive_scan(local, tmp, Z);
+      __syncthreads();
+    }
+    if (Z > 0.f) {
+      const float target = u * Z;
+      const Found chunk = block_find_first(a.nRC, [&](int c) { return rm[c]; }, target, tmp);
+      const int v0 = chunk.idx * kResidChunk;
+      const int nv = min(kResidChunk, a.V - v0);
+      const Found in = block_find_first(
+          nv,
+          [&](int i) {
+            return fmaxf(expf(Lp[v0 + i] - lse_p) - expf(Lq[v0 + i] - lse_q), 0.f);
+          },
+          target - chunk.before, tmp);
+      z = v0 + in.idx;
+    } else {
+      // residual mass vanished in rounding although a rejection occurred: commit argmax pi
+      float best = -INFINITY;
+      int bi = INT_MAX;
+      for (int v = tid; v < a.V; v += NT) {
+        const float l = Lp[v];
+        if (l > best) { best = l; bi = v; }
+      }
+      const float gbest = block_max(best, tmp);
+      z = block_min_int(best == gbest ? bi : INT_MAX, tmp);
+    }
+    z_conf = expf(Lp[z] - lse_p);
+  }
+
+  // commit tokens and confidences
+  const int committed = min(acc_len + 1, window);
+  if (tid < a.K) {
+    const int s = b * a.K + tid;
+    int tok = -1;
+    float c = 0.f;
+    if (tid < acc_len) { tok = a.xdraft[s]; c = a.ptok[s]; }
+    else if (tid == acc_len && acc_len < window) { tok = z; c = z_conf; }
+    a.out_tokens[s] = tok;
+    if (a.diag_conf_tok) a.diag_conf_tok[s] = c;
+  }
+  if (tid == 0) a.out_accept_len[b] = acc_len;
+
+  // block state: mask, pass set, confidences
+  const size_t row = (size_t)b * a.block;
+  for (int i = tid; i < a.block; i += NT) {
+    s_mask[i] = a.mask_in ? (a.mask_in[row + i] != 0) : 1;
+    s_cand[i] = a.pass_mask ? (a.pass_mask[row + i] != 0) : 0;
+    s_conf[i] = a.conf ? a.conf[row + i] : 0.f;
+  }
+  __syncthreads();
+  if (tid < committed) {
+    const int s = b * a.K + tid;
+    const int pos = a.slot_pos[s];
+    s_mask[pos] = 0;
+    s_cand[pos] = 1;
+    s_conf[pos] = (tid < acc_len) ? a.ptok[s] : z_conf;
+  }
+  __syncthreads();
+  int unresolved = 0;
+  for (int i = tid; i < a.block; i += NT) unresolved |= s_mask[i];
+  unresolved = block_max_int(unresolved, tmp);
+
+  const bool fire = !unresolved && !a.final_pass;
+  if (fire) {
+    // LowConf: rank every candidate by (confidence, position); the n_rm lowest are re-masked
+    const int n_rm = a.n_rm < 0 ? a.block / 2 : a.n_rm;
+    for (int i = tid; i < a.block; i += NT) {
+      const bool cand_i = a.lowconf_scope ? true : (s_cand[i] != 0);
+      if (!cand_i) continue;
+      const float ci = s_conf[i];
+      int rank = 0;
+      for (int j = 0; j < a.block; ++j) {
+        const bool cand_j = a.lowconf_scope ? true : (s_cand[j] != 0);
+        const float cj = s_conf[j];
+        rank += (cand_j && (cj < ci || (cj == ci && j < i))) ? 1 : 0;
+      }
+      if (rank < n_rm) s_mask[i] = 1;
+    }
+    __syncthreads();
+  }
+  for (int i = tid; i < a.block; i += NT) {
+    a.out_remask[row + i] = s_mask[i];
+    if (a.pass_mask) a.pass_mask[row + i] = fire ? 0 : s_cand[i];
+    if (a.conf) a.conf[row + i] = s_conf[i];
+  }
+}
+
+__global__ void copy_logits_kernel(const float* __restrict__ src, long ldl, float* __restrict__ dst,
+                                   int V, long rows) {
+  const long n = rows * V;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    const long r = i / V, v = i - r * V;
+    dst[i] = src[r * ldl + v];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_verify(const VerifyArgs& a) {
+  const int M = 2 * a.B * a.K;
+  hipLaunchKernelGGL(row_lse_draft_kernel, dim3(M), dim3(NT), 0, a.stream, a);
+  const int gx = (a.nRC + NW - 1) / NW;
+  const int nslots = a.all_slots ? a.B * a.K : a.B;
+  hipLaunchKernelGGL(accept_resid_kernel, dim3(nslots, gx), dim3(NT), 0, a.stream, a);
+  hipLaunchKernelGGL(finalize_kernel, dim3(a.B), dim3(NT), 0, a.stream, a);
+  if (a.diag_logits) {
+    const long rows = M;
+    const long n = rows * a.V;
+    const int blocks = (int)((n + 255) / 256 > 65535 ? 65535 : (n + 255) / 256);
+    hipLaunchKernelGGL(copy_logits_kernel, dim3(blocks), dim3(256), 0, a.stream, a.logits, a.ldl,
+                       a.diag_logits, a.V, rows);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace fef

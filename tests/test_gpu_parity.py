@@ -1,0 +1,299 @@
+"""GPU parity: the HIP verify step, called through the C ABI, against the CPU oracle on the
+same seeded inputs (see tests/parity.py for the comparison protocol and tolerances)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fef_oracle as O
+from paper_2605_14305_amd import binding as fb
+from paper_2605_14305_amd import synth
+import parity
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def run_case(B, K, block, d, V, dtype="bf16", seed=0, rho=0.9, logit_std=3.0, variant=fb.FEF_GEMM_AUTO,
+             temperature=1.0, step=0, seq_base=0, pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0,
+             mask=None, pass_mask=None, conf=None, draft_tokens=None, with_logits=True, W=None,
+             hidden=None, logit_atol=2e-4):
+    wl_sigma = logit_std / (0.02 * np.sqrt(d)) if logit_std > 0 else 1.0
+    if W is None:
+        W = synth.make_head(V, d, seed, dtype)
+    hd, ht = hidden if hidden is not None else synth.make_hidden(B, K, d, seed, rho, wl_sigma, dtype, 0, step)
+    vs = fb.VerifyStep(B, K, block, d, V, dtype=dtype, device=DEV, diag=True, diag_logits=with_logits,
+                       gemm_variant=variant)
+    dev = lambda a, dt: None if a is None else torch.as_tensor(np.ascontiguousarray(a), dtype=dt).to(DEV)
+    g_mask, g_pm, g_cf = dev(mask, torch.uint8), dev(pass_mask, torch.uint8), dev(conf, torch.float32)
+    g_dt = dev(draft_tokens, torch.int32)
+    tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), W.to(DEV), seed, temperature=temperature, step=step,
+                       seq_base=seq_base, pos_base=pos_base, n_rm=n_rm, final_pass=final_pass,
+                       lowconf_scope=lowconf_scope, mask_in=g_mask, pass_mask=g_pm, conf=g_cf,
+                       draft_tokens=g_dt)
+    torch.cuda.synchronize()
+    ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), synth.to_f64(W), K, block, seed,
+                        temperature=temperature, step=step, seq_base=seq_base, pos_base=pos_base,
+                        n_rm=n_rm, final_pass=final_pass, lowconf_scope=lowconf_scope, mask_in=mask,
+                        pass_mask=pass_mask, conf=None if conf is None else np.asarray(conf, np.float32),
+                        draft_tokens=draft_tokens, return_logits=with_logits)
+    diag = {k: _np(v) for k, v in vs.diag.items()}
+    stats = parity.compare(ref, _np(tok), _np(acc), _np(rem), diag, drafts_given=draft_tokens is not None,
+                           logit_atol=logit_atol)
+    out = {"tokens": _np(tok), "accept_len": _np(acc), "remask": _np(rem), "diag": diag,
+           "pass_mask": None if g_pm is None else _np(g_pm), "conf": None if g_cf is None else _np(g_cf)}
+    return ref, out, stats
+
+
+def _check_state(ref, out):
+    """in/out state arrays after a compared call."""
+    if out["pass_mask"] is not None:
+        assert np.array_equal(out["pass_mask"], ref.pass_mask)
+    if out["conf"] is not None:
+        assert np.allclose(out["conf"], ref.conf, rtol=2e-4, atol=1e-12)
+
+
+def test_tiny_configuration_f32_all_blocks_and_steps():
+    """Tiny instance: batch 1, block 8, K=4, d=64, V=32 and V=8, fp32 head, seed 0."""
+    for name in ("tiny", "tiny_v8"):
+        wl = synth.WORKLOADS[name]
+        W = synth.make_head(wl.V, wl.d, 0, "f32")
+        total = {"near_margin": 0, "compared": 0}
+        for blk in range(wl.gen_len // wl.block):
+            for step in range(16):
+                hidden = synth.make_round(wl, 0, blk, step)
+                ref, out, st = run_case(wl.B, wl.K, wl.block, wl.d, wl.V, "f32", seed=0, W=W, hidden=hidden,
+                                        step=step, pos_base=blk * wl.block, logit_atol=1e-5)
+                for k in total:
+                    total[k] += st[k]
+        assert total["compared"] >= 0.9 * (total["compared"] + total["near_margin"])
+
+
+def test_tiny_scaled_logits_exercise_rejections():
+    # the stated tiny scale (logit std ~0.16) almost never rejects; a wider one does
+    rej = 0
+    for step in range(12):
+        ref, out, st = run_case(4, 4, 8, 64, 32, "f32", seed=3, rho=0.5, logit_std=2.0, step=step)
+        rej += int((ref.accept_len < ref.window).sum())
+        assert st["near_margin"] <= 1
+    assert rej > 10
+
+
+@pytest.mark.parametrize("K,V", [(8, 1000), (5, 4099), (8, 16), (3, 7)])
+def test_skinny_kernel_small_shapes(K, V):
+    near = 0
+    for step in range(4):
+        ref, out, st = run_case(1, K, 16, 512, V, seed=11, rho=0.8, step=step, variant=fb.FEF_GEMM_SKINNY)
+        near += st["near_margin"]
+    assert near <= 1
+
+
+@pytest.mark.parametrize("B,K,d,V", [(5, 8, 64, 1000), (20, 8, 512, 777), (3, 16, 3584, 2050),
+                                     (70, 2, 128, 300), (1, 1, 64, 1)])
+def test_tiled_kernel_small_shapes(B, K, d, V):
+    ref, out, st = run_case(B, K, max(K, 16), d, V, seed=12, rho=0.8, variant=fb.FEF_GEMM_TILED)
+    assert st["near_margin"] <= max(1, B // 10)
+
+
+def test_skinny_and_tiled_agree():
+    W = synth.make_head(3000, 512, 5)
+    hidden = synth.make_hidden(1, 8, 512, 5, 0.7, 3.0 / (0.02 * np.sqrt(512)))
+    a = run_case(1, 8, 32, 512, 3000, seed=5, W=W, hidden=hidden, variant=fb.FEF_GEMM_SKINNY)
+    b = run_case(1, 8, 32, 512, 3000, seed=5, W=W, hidden=hidden, variant=fb.FEF_GEMM_TILED)
+    assert np.abs(a[1]["diag"]["logits"] - b[1]["diag"]["logits"]).max() < 1e-4
+    if a[2]["near_margin"] == 0 and b[2]["near_margin"] == 0:
+        assert np.array_equal(a[1]["tokens"], b[1]["tokens"])
+
+
+def test_deterministic_bits():
+    W = synth.make_head(5000, 512, 1).to(DEV)
+    hd, ht = (t.to(DEV) for t in synth.make_hidden(2, 4, 512, 1, 0.8, 3.0 / (0.02 * np.sqrt(512))))
+    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED):
+        outs = []
+        for rep in range(3):
+            vs = fb.VerifyStep(2, 4, 8, 512, 5000, diag=True, diag_logits=True, gemm_variant=variant)
+            vs.workspace.fill_(rep * 37)        # stale workspace contents must not matter
+            tok, acc, rem = vs(hd, ht, W, 42, step=rep * 0 + 9)
+            torch.cuda.synchronize()
+            outs.append((_np(tok).copy(), _np(acc).copy(), _np(rem).copy(), _np(vs.diag["logits"]).copy(),
+                         _np(vs.diag["alpha"]).copy()))
+        for o in outs[1:]:
+            for x, y in zip(o, outs[0]):
+                assert np.array_equal(x, y)
+
+
+def test_temperature_step_and_bases():
+    ref, out, st = run_case(3, 4, 16, 512, 2000, seed=21, temperature=0.5, step=77, seq_base=1000,
+                            pos_base=4096, rho=0.95, variant=fb.FEF_GEMM_TILED)
+    assert st["near_margin"] <= 1
+    # batch invariance on the device: sequence 2 alone, addressed by seq_base, gives the same row
+    W = synth.make_head(2000, 512, 21)
+    hd, ht = synth.make_hidden(3, 4, 512, 21, 0.95, 3.0 / (0.02 * np.sqrt(512)), "bf16", 0, 77)
+    ref1, out1, st1 = run_case(1, 4, 16, 512, 2000, seed=21, temperature=0.5, step=77, seq_base=1002,
+                               pos_base=4096, W=W, hidden=(hd[2:3].contiguous(), ht[2:3].contiguous()),
+                               variant=fb.FEF_GEMM_TILED)
+    assert np.array_equal(out1["tokens"][0], out["tokens"][2])
+    assert out1["accept_len"][0] == out["accept_len"][2]
+
+
+def test_masks_window_boundary_and_supplied_drafts():
+    B, K, block, d, V = 6, 4, 8, 512, 600
+    mask = np.array([[1, 1, 1, 1, 1, 1, 1, 1],
+                     [0, 0, 1, 0, 1, 0, 0, 1],
+                     [0, 0, 0, 0, 0, 0, 1, 0],
+                     [0, 0, 0, 0, 0, 0, 0, 0],
+                     [1, 0, 1, 0, 1, 0, 1, 0],
+                     [0, 1, 1, 1, 1, 1, 1, 1]], np.uint8)
+    ref, out, st = run_case(B, K, block, d, V, seed=31, rho=0.6, mask=mask, final_pass=True,
+                            pass_mask=np.zeros((B, block), np.uint8), conf=np.zeros((B, block), np.float32))
+    assert ref.window.tolist() == [4, 3, 1, 0, 4, 4]
+    assert st["near_margin"] <= 1
+    if st["near_margin"] == 0:
+        _check_state(ref, out)
+    drafts = np.random.default_rng(0).integers(0, V, size=(B, K)).astype(np.int32)
+    ref, out, st = run_case(B, K, block, d, V, seed=31, rho=0.6, mask=mask, draft_tokens=drafts)
+    assert np.array_equal(out["diag"]["draft_tokens"][ref.slot_pos >= 0], drafts[ref.slot_pos >= 0])
+    assert st["near_margin"] <= 1
+
+
+@pytest.mark.parametrize("scope", [0, 1])
+def test_low_confidence_remask_fires_when_block_resolves(scope):
+    B, K, block, d, V = 8, 4, 8, 512, 500
+    rng = np.random.default_rng(5)
+    mask = np.zeros((B, block), np.uint8)
+    pm = np.zeros((B, block), np.uint8)
+    for b in range(B):
+        unresolved = rng.choice(block, size=1 + b % 3, replace=False)   # 1..3 left: may resolve now
+        mask[b, unresolved] = 1
+        pm[b, rng.choice(np.setdiff1d(np.arange(block), unresolved), size=3, replace=False)] = 1
+    conf = rng.random((B, block)).astype(np.float32)
+    fired = 0
+    for n_rm in (-1, 2, 0, 100):
+        ref, out, st = run_case(B, K, block, d, V, seed=41, rho=0.9, mask=mask, pass_mask=pm, conf=conf,
+                                n_rm=n_rm, lowconf_scope=scope)
+        resolved = (ref.remask.sum(1) > 0) & ((mask.sum(1) - ref.committed) == 0)
+        fired += int(resolved.sum())
+        if st["near_margin"] == 0 and st["remask_skipped"] == 0:
+            _check_state(ref, out)
+    assert fired > 0
+    ref, out, st = run_case(B, K, block, d, V, seed=41, rho=0.9, mask=mask, pass_mask=pm, conf=conf,
+                            n_rm=3, lowconf_scope=scope, final_pass=True)
+    assert np.all(out["remask"] <= mask)
+
+
+def test_stateful_pass_over_a_block_matches_oracle():
+    """Rounds chained through mask / pass_mask / conf on each side separately until the block
+    resolves and LowConf fires; then a second pass over the re-masked positions."""
+    B, K, block, d, V = 4, 4, 16, 512, 800
+    W = synth.make_head(V, d, 7)
+    Wd, W64 = W.to(DEV), synth.to_f64(W)
+    vs = fb.VerifyStep(B, K, block, d, V, device=DEV, diag=True)
+    g_mask = torch.ones(B, block, dtype=torch.uint8, device=DEV)
+    g_pm = torch.zeros(B, block, dtype=torch.uint8, device=DEV)
+    g_cf = torch.zeros(B, block, dtype=torch.float32, device=DEV)
+    o_mask, o_pm, o_cf = np.ones((B, block), np.uint8), np.zeros((B, block), np.uint8), np.zeros((B, block))
+    alive = np.ones(B, bool)          # sequences still in lock-step with the oracle
+    sigma = 3.0 / (0.02 * np.sqrt(d))
+    refired = 0
+    for step in range(24):
+        hd, ht = synth.make_hidden(B, K, d, 7, 0.85, sigma, "bf16", 0, step)
+        tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 7, step=step, mask_in=g_mask, pass_mask=g_pm,
+                           conf=g_cf, n_rm=5)
+        torch.cuda.synchronize()
+        ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), W64, K, block, 7, step=step, mask_in=o_mask,
+                            pass_mask=o_pm, conf=o_cf, n_rm=5)
+        st = parity.compare(ref, _np(tok), _np(acc), _np(rem))
+        for b in range(B):
+            near = (ref.draft_gap[b] < parity.TOL_CDF).any() or (ref.accept_margin[b] < parity.TOL_ACCEPT).any() \
+                or ref.resid_gap[b] < parity.TOL_CDF or ref.lowconf_gap[b] < parity.TOL_CONF
+            if near:
+                alive[b] = False
+            if alive[b]:
+                assert np.array_equal(_np(rem)[b], ref.remask[b])
+                assert np.array_equal(_np(g_pm)[b], ref.pass_mask[b])
+                assert np.allclose(_np(g_cf)[b], ref.conf[b], rtol=2e-4, atol=1e-12)
+                refired += int(o_mask[b].sum() - ref.committed[b] == 0)
+        g_mask = rem.clone()
+        o_mask, o_pm, o_cf = ref.remask, ref.pass_mask, ref.conf
+        # keep dropped sequences from drifting: re-seed their device state from the oracle's
+        for b in np.flatnonzero(~alive):
+            g_mask[b] = torch.as_tensor(o_mask[b]).to(DEV)
+            g_pm[b] = torch.as_tensor(o_pm[b]).to(DEV)
+            g_cf[b] = torch.as_tensor(o_cf[b].astype(np.float32)).to(DEV)
+            alive[b] = True
+    assert refired >= B          # every sequence resolved its block at least once
+
+
+@pytest.fixture(scope="module")
+def llada_head():
+    wl = synth.WORKLOADS["llada_b1"]
+    W = synth.make_head(wl.V, wl.d, 0, "bf16")
+    return wl, W, W.to(DEV), synth.to_f64(W)
+
+
+def test_llada_shape_batch1_full_size(llada_head):
+    """LLaDA-8B-shaped single sequence (d=4096, V=126464, K=8, block 32) in the configuration
+    the benchmark times, every element of the outputs against the oracle."""
+    wl, W, Wd, W64 = llada_head
+    vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, device=DEV, diag=True, diag_logits=True)
+    assert fb.fef_select_gemm(vs._params(), wl.K) == fb.FEF_GEMM_SKINNY
+    near = compared = 0
+    acc_lens = []
+    for step in range(6):
+        hd, ht = synth.make_round(wl, 0, block_index=step % 2, step=step)
+        tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 0, step=step, pos_base=32 * (step % 2))
+        torch.cuda.synchronize()
+        ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), W64, wl.K, wl.block, 0, step=step,
+                            pos_base=32 * (step % 2), return_logits=True)
+        st = parity.compare(ref, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs.diag.items()})
+        near += st["near_margin"]; compared += st["compared"]
+        acc_lens.append(int(ref.accept_len[0]))
+        print(f"step {step}: accept_len {ref.accept_len[0]} alpha {ref.alpha[0].round(3)} {st}", flush=True)
+    assert compared >= 4
+    assert 0 < np.mean(acc_lens) < wl.K       # the recipe gives a mix of acceptances and rejections
+
+
+def test_llada_shape_batched_subset(llada_head):
+    """B=16 at full d and V through the tiled kernel; the oracle checks a seeded subset of
+    sequences, which is valid because a sequence's outcome depends only on its own rows and
+    (seed, sequence id, step, position)."""
+    wl, W, Wd, W64 = llada_head
+    B, K, block = 16, 8, 32
+    vs = fb.VerifyStep(B, K, block, wl.d, wl.V, device=DEV, diag=True)
+    hd, ht = synth.make_hidden(B, K, wl.d, 3, wl.rho, wl.sigma_h, "bf16", 0, 5)
+    tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 3, step=5)
+    torch.cuda.synchronize()
+    # sequence ids differ per picked row, so the oracle runs them one at a time with seq_base
+    for b in [0, 7, 15]:
+        r = O.verify_step(synth.to_f64(hd[b:b + 1]), synth.to_f64(ht[b:b + 1]), W64, K, block, 3, step=5,
+                          seq_base=b)
+        diag = {k: _np(v)[b:b + 1] if k != "lse" else _np(v)[:, b:b + 1] for k, v in vs.diag.items()}
+        st = parity.compare(r, _np(tok)[b:b + 1], _np(acc)[b:b + 1], _np(rem)[b:b + 1], diag)
+        print(f"seq {b}: {st}", flush=True)
+
+
+def test_dream_shape_subset():
+    """Dream-7B-shaped rows (d=3584, V=151936, K=16) through both bf16 kernels."""
+    wl = synth.WORKLOADS["dream_b32"]
+    W = synth.make_head(wl.V, wl.d, 1, "bf16")
+    Wd, W64 = W.to(DEV), synth.to_f64(W)
+    B = 4
+    vs = fb.VerifyStep(B, wl.K, wl.block, wl.d, wl.V, device=DEV, diag=True)
+    hd, ht = synth.make_round(wl, 1, 0, 2, B=B)
+    tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 1, step=2)
+    torch.cuda.synchronize()
+    ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), W64, wl.K, wl.block, 1, step=2)
+    st = parity.compare(ref, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs.diag.items()})
+    print(st, flush=True)
+    assert st["compared"] >= 2
+    # skinny kernel at d=3584: one sequence, K=8
+    vs1 = fb.VerifyStep(1, 8, wl.block, wl.d, wl.V, device=DEV, diag=True, gemm_variant=fb.FEF_GEMM_SKINNY)
+    hd1, ht1 = hd[:1, :8].contiguous(), ht[:1, :8].contiguous()
+    tok, acc, rem = vs1(hd1.to(DEV), ht1.to(DEV), Wd, 1, step=2)
+    torch.cuda.synchronize()
+    ref1 = O.verify_step(synth.to_f64(hd1), synth.to_f64(ht1), W64, 8, wl.block, 1, step=2)
+    parity.compare(ref1, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs1.diag.items()})
