@@ -22,10 +22,10 @@ fef_status fail(fef_status s, const char* fmt, ...) {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  int variant, tn, nT, nRC, all_slots;
+  int variant, nT, tile_unit, tile_T, nRC, all_slots;
   long ldl;
-  size_t off_logits, off_partials, off_lse, off_xdraft, off_slot_pos, off_window, off_acc,
-      off_ptok, off_rmass, off_amass, total;
+  size_t off_logits, off_partials, off_lse, off_xdraft, off_slot_pos, off_window, off_counters,
+      off_rmass, off_amass, total;
 };
 
 // Sizes only; no pointer checks.
@@ -86,8 +86,15 @@ fef_status make_layout(const fef_params* p, int32_t K, int32_t block, Layout* L)
   s = select_variant(p, K, &L->variant);
   if (s != FEF_OK) return s;
   const size_t BK = (size_t)p->B * K, M = 2 * BK;
-  L->tn = L->variant == FEF_GEMM_SKINNY ? fef::kSkinnyTn : fef::kTiledTn;
-  L->nT = (p->V + L->tn - 1) / L->tn;
+  if (L->variant == FEF_GEMM_SKINNY) {
+    // one partial per (row, workgroup); a workgroup's tokens are a contiguous run of 16-token tiles
+    L->tile_unit = fef::kSkinnyUnit;
+    L->tile_T = (p->V + fef::kSkinnyUnit - 1) / fef::kSkinnyUnit;
+    L->nT = L->tile_T < fef::kSkinnyMaxGrid ? L->tile_T : fef::kSkinnyMaxGrid;
+  } else {
+    L->tile_unit = fef::kTiledTn;
+    L->tile_T = L->nT = (p->V + fef::kTiledTn - 1) / fef::kTiledTn;
+  }
   L->nRC = (p->V + fef::kResidChunk - 1) / fef::kResidChunk;
   L->ldl = (long)align_up((size_t)p->V, 64);
   L->all_slots = (p->diag_alpha || p->diag_resid_mass) ? 1 : 0;
@@ -100,8 +107,7 @@ fef_status make_layout(const fef_params* p, int32_t K, int32_t block, Layout* L)
   L->off_xdraft = take(BK * sizeof(int32_t));
   L->off_slot_pos = take(BK * sizeof(int32_t));
   L->off_window = take((size_t)p->B * sizeof(int32_t));
-  L->off_acc = take((size_t)p->B * sizeof(int32_t));
-  L->off_ptok = take(BK * sizeof(float));
+  L->off_counters = take((size_t)p->B * sizeof(int32_t));
   L->off_rmass = take(nslots * (size_t)L->nRC * sizeof(float));
   L->off_amass = take(L->all_slots ? nslots * (size_t)L->nRC * sizeof(float) : 0);
   L->total = o;
@@ -168,7 +174,8 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   fef::VerifyArgs v;
   memset(&v, 0, sizeof v);
   v.B = prm->B; v.K = K; v.block = block; v.V = prm->V;
-  v.ldl = L.ldl; v.logits = h.logits; v.partials = h.partials; v.nT = L.nT; v.tn = L.tn;
+  v.ldl = L.ldl; v.logits = h.logits; v.partials = h.partials; v.nT = L.nT;
+  v.tile_unit = L.tile_unit; v.tile_T = L.tile_T; v.tile_G = L.nT;
   v.seed = seed; v.step = prm->step; v.seq_base = prm->seq_base; v.pos_base = prm->pos_base;
   v.n_rm = prm->n_rm; v.final_pass = prm->final_pass; v.lowconf_scope = prm->lowconf_scope;
   v.mask_in = prm->mask_in; v.pass_mask = prm->pass_mask; v.conf = prm->conf;
@@ -177,8 +184,7 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   v.xdraft = (int32_t*)(ws + L.off_xdraft);
   v.slot_pos = (int32_t*)(ws + L.off_slot_pos);
   v.window = (int32_t*)(ws + L.off_window);
-  v.accept_len_ws = (int32_t*)(ws + L.off_acc);
-  v.ptok = (float*)(ws + L.off_ptok);
+  v.counters = (int32_t*)(ws + L.off_counters);
   v.rmass = (float*)(ws + L.off_rmass);
   v.amass = (float*)(ws + L.off_amass);
   v.nRC = L.nRC; v.all_slots = L.all_slots;

@@ -59,8 +59,10 @@ struct HeadArgs {
   hipStream_t stream;
 };
 
-constexpr int kSkinnyTn = 16;  // partial-tile width written by the skinny kernel
-constexpr int kTiledTn = 64;   // ... by the tiled and f32 kernels
+constexpr int kSkinnyUnit = 16;     // the skinny kernel walks W in tiles of 16 tokens ...
+constexpr int kSkinnyMaxGrid = 256;  // ... split evenly over at most one workgroup per CU, and
+                                     // writes one partial per (row, workgroup)
+constexpr int kTiledTn = 64;         // partial-tile width of the tiled and f32 kernels
 
 bool skinny_supports(int M, int d);
 hipError_t launch_head_skinny(const HeadArgs& a);
@@ -77,7 +79,8 @@ struct VerifyArgs {
   long ldl;
   const float* logits;      // [2*B*K, ldl]
   const float2* partials;   // [2*B*K, nT]
-  int nT, tn;
+  int nT;                   // partial tiles per row
+  int tile_unit, tile_T, tile_G;  // tile i covers tokens [unit*floor(i*T/G), unit*floor((i+1)*T/G))
   uint64_t seed;
   uint32_t step, seq_base, pos_base;
   int n_rm, final_pass, lowconf_scope;
@@ -90,8 +93,7 @@ struct VerifyArgs {
   int32_t* xdraft;          // [B*K]
   int32_t* slot_pos;        // [B*K]
   int32_t* window;          // [B]
-  int32_t* accept_len_ws;   // [B]
-  float* ptok;              // [B*K] pi(x~)
+  int32_t* counters;        // [B] completion tickets of accept_resid_kernel
   float* rmass;             // [nslots, nRC] residual mass per chunk
   float* amass;             // [nslots, nRC] overlap mass per chunk (all_slots only)
   int nRC;                  // ceil(V / kResidChunk)

@@ -5,10 +5,12 @@
 // which the row's log-sum-exp is merged later.
 //
 //   head_skinny_kernel  M = 2*B*K <= 16.  HBM-bound: W (about 1 GB) is streamed exactly once.
-//                       Eight wavefronts split k; each keeps its slice of H in registers as
+//                       One workgroup per CU owns a contiguous run of 16-token tiles.  Its
+//                       eight wavefronts split k; each keeps its slice of H in registers as
 //                       the MFMA B operand for the whole kernel, streams its 1 KB slice of
 //                       sixteen W rows straight into the MFMA A operand registers one tile
 //                       ahead, and the eight partial 16x16 tiles are summed through LDS.
+//                       One (max, sum exp) partial per (row, workgroup).
 //   head_tiled_kernel   any M.  128x128x64 LDS-tiled MFMA GEMM, XCD-aware tile order so the
 //                       workgroups that share a W tile run on the same L2.
 //   head_f32_kernel     fp32 inputs, plain FMA; tiny instances only.
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
     for (int s = 0; s < KS; ++s) buf[s] = *reinterpret_cast<const bf16x8*>(wp + 32 * s);
   };
 
-  auto compute_tile = [&](int t, const bf16x8(&buf)[KS], int par) {
+  auto compute_tile = [&](int t, const bf16x8(&buf)[KS], int par, float& run_m, float& run_s) {
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s)
@@ -98,20 +100,26 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
       float e = valid ? __expf(logit - mx) : 0.f;
 #pragma unroll
       for (int off = 8; off >= 1; off >>= 1) e += __shfl_xor(e, off, 64);
-      if (vl == 0 && m < M) a.partials[(size_t)m * a.nT + t] = make_float2(mx, e);
+      if (mx > run_m) { run_s = run_s * __expf(run_m - mx) + e; run_m = mx; }
+      else if (mx > -INFINITY) run_s += e * __expf(mx - run_m);
     }
   };
+
+  // running (max, sum exp) of this workgroup's tokens, per row, replicated over the row's 16 lanes
+  float run_m = -INFINITY, run_s = 0.f;
 
   bf16x8 buf0[KS], buf1[KS];
   if (t0 < t1) load_tile(t0, buf0);
   for (int t = t0; t < t1; t += 2) {
     if (t + 1 < t1) load_tile(t + 1, buf1);
-    compute_tile(t, buf0, 0);
+    compute_tile(t, buf0, 0, run_m, run_s);
     if (t + 1 < t1) {
       if (t + 2 < t1) load_tile(t + 2, buf0);
-      compute_tile(t + 1, buf1, 1);
+      compute_tile(t + 1, buf1, 1, run_m, run_s);
     }
   }
+  if (tid < 256 && (tid & 15) == 0 && (tid >> 4) < M)
+    a.partials[(size_t)(tid >> 4) * a.nT + blockIdx.x] = make_float2(run_m, run_s);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -247,26 +255,13 @@ __global__ __launch_bounds__(kWave) void head_f32_kernel(HeadArgs a) {
   if (lane == 0) a.partials[(size_t)r * a.nT + t] = make_float2(mx, e);
 }
 
-int compute_units() {
-  static int cached = 0;
-  if (!cached) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cached = n;
-    else
-      cached = 256;
-  }
-  return cached;
-}
-
 }  // namespace
 
 bool skinny_supports(int M, int d) { return M <= 16 && (d == 512 || d == 3584 || d == 4096); }
 
 hipError_t launch_head_skinny(const HeadArgs& a) {
-  const int tiles = (a.V + 15) / 16;
-  const int grid = tiles < compute_units() ? tiles : compute_units();
+  const int tiles = (a.V + kSkinnyUnit - 1) / kSkinnyUnit;
+  const int grid = a.nT;  // = min(tiles, kSkinnyMaxGrid): one partial per (row, workgroup)
   switch (a.d) {
     case 512:
       hipLaunchKernelGGL(head_skinny_kernel<2>, dim3(grid), dim3(kSkinnyThreads), 0, a.stream, a, tiles);

@@ -1,19 +1,20 @@
 // Sampling and verification kernels that follow the vocabulary head (Algorithm 2 of the
 // paper, lines "Sample draft tokens" to "break", and the LowConf re-corruption):
 //
-//   row_lse_draft_kernel   one workgroup per logits row: merge the per-tile (max, sum exp)
-//                          partials into the row's log-sum-exp; draft rows also locate their
-//                          window slot and draw x~ ~ rho by a two-level inverse CDF.
-//   accept_resid_kernel    per sequence: accept tests u <= min{1, pi(x~)/rho(x~)}, first
-//                          rejection by ballot; then per 256-token chunk the residual mass
-//                          sum [pi - rho]_+ (and the overlap mass sum min{pi, rho}) of the
-//                          rejected slot.
-//   finalize_kernel        per sequence: inverse CDF over the residual chunks and inside the
-//                          selected chunk, commit tokens and confidences, update the block
-//                          mask and apply LowConf.
+//   row_lse_draft_kernel     one wavefront per logits row: merge the head kernel's per-tile
+//                            (max, sum exp) partials into the row's log-sum-exp; draft rows
+//                            also locate their window slot and draw x~ ~ rho by a two-level
+//                            inverse CDF (tiles, then tokens inside the tile).
+//   accept_resid_kernel      per sequence: accept tests u <= min{1, pi(x~)/rho(x~)}, first
+//                            rejection by ballot; per 256-token chunk the residual mass
+//                            sum [pi - rho]_+ (and the overlap mass sum min{pi, rho}) of the
+//                            rejected slot.  The workgroup that finishes a sequence's last
+//                            chunk (ticket counter) goes on to the final phase: inverse CDF
+//                            over the residual chunks and inside the selected chunk, commit
+//                            of tokens and confidences, block-mask update and LowConf.
 //
-// Every floating-point reduction uses a fixed tree (no atomics), so results are reproducible
-// bit for bit.
+// Every floating-point reduction uses a fixed tree (no float atomics), so results are
+// reproducible bit for bit.
 #include <limits.h>
 #include <math.h>
 
@@ -161,15 +162,67 @@ __device__ inline Found block_find_first(int n, F mass, float target, BlockTmp& 
   return f;
 }
 
+// Token range of partial tile i: [unit * floor(i T / G), unit * floor((i+1) T / G)) within [0, V).
+__device__ inline int tile_start(const VerifyArgs& a, int i) {
+  return (int)((long)i * a.tile_T / a.tile_G) * a.tile_unit;
+}
+
+// Wavefront version of block_find_first: lane l owns the contiguous segment [l*per, (l+1)*per).
+template <class F>
+__device__ inline Found wave_find_first(int n, F mass, float target) {
+  const int lane = threadIdx.x & 63;
+  const int per = (n + kWave - 1) / kWave;
+  const int begin = min(n, lane * per), end = min(n, begin + per);
+  float local = 0.f;
+  for (int i = begin; i < end; ++i) local += mass(i);
+  float inc = local;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const float y = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += y;
+  }
+  float exc = __shfl_up(inc, 1, 64);
+  if (lane == 0) exc = 0.f;
+  float run = exc, before = 0.f, before_pos = 0.f;
+  int cand = INT_MAX, last_pos = -1;
+  for (int i = begin; i < end; ++i) {
+    const float mi = mass(i);
+    const float nxt = run + mi;
+    if (mi > 0.f) { last_pos = i; before_pos = run; }
+    if (cand == INT_MAX && nxt >= target) { cand = i; before = run; }
+    run = nxt;
+  }
+  int win = wave_min_int(cand);
+  bool mine = cand != INT_MAX && cand == win;
+  if (win == INT_MAX) {  // target not reached: fall back to the last positive mass
+    const int lp = wave_max_int(last_pos);
+    if (lp < 0) { win = 0; mine = lane == 0; before = 0.f; }
+    else { win = lp; mine = last_pos == lp; before = before_pos; }
+  }
+  const unsigned long long owner = __ballot(mine);
+  Found f;
+  f.idx = win;
+  f.before = __shfl(before, __ffsll((long long)owner) - 1, 64);
+  f.total = __shfl(inc, 63, 64);
+  return f;
+}
+
+// Loads that must observe what other workgroups of the same kernel wrote before taking their
+// ticket: relaxed atomic loads at device scope are served by the L2, not by this CU's cache.
+__device__ inline float coherent_load(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ---------------------------------------------------------------------------------------------
-// Kernel 1: per-row log-sum-exp, window slot, draft sample.
+// Kernel 1: per-row log-sum-exp, window slot, draft sample.  One wavefront per row.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
-  __shared__ BlockTmp tmp;
-  __shared__ int s_pos, s_cnt;
-  const int tid = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int BK = a.B * a.K;
-  const int r = blockIdx.x;
+  if (blockIdx.x == 0)  // tickets of the next kernel start at zero
+    for (int i = threadIdx.x; i < a.B; i += NT) a.counters[i] = 0;
+  const int r = blockIdx.x * NW + wave;
+  if (r >= 2 * BK) return;
   const bool is_draft = r < BK;
   const int s = is_draft ? r : r - BK;
   const int b = s / a.K, m = s % a.K;
@@ -177,159 +230,75 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
   // log-sum-exp of the row from the head kernel's per-tile partials
   const float2* P = a.partials + (size_t)r * a.nT;
   float mx = -INFINITY;
-  for (int t = tid; t < a.nT; t += NT) mx = fmaxf(mx, P[t].x);
-  mx = block_max(mx, tmp);
+  for (int t = lane; t < a.nT; t += kWave) mx = fmaxf(mx, P[t].x);
+  mx = wave_max(mx);
   float sm = 0.f;
-  for (int t = tid; t < a.nT; t += NT) {
+  for (int t = lane; t < a.nT; t += kWave) {
     const float2 p = P[t];
     sm += p.y * expf(p.x - mx);
   }
-  sm = block_sum(sm, tmp);
+  sm = wave_sum(sm);
   const float lse = mx + logf(sm);
-  if (tid == 0) {
+  if (lane == 0) {
     a.lse[r] = lse;
     if (a.diag_lse) a.diag_lse[r] = lse;
   }
   if (!is_draft) return;
 
   // window slot m = (m+1)-th unresolved position of the block, ascending
-  if (tid < kWave) {
-    int cnt = 0, pos = -1;
-    for (int base = 0; base < a.block; base += kWave) {
-      const int i = base + tid;
-      const bool bit = i < a.block && (a.mask_in ? a.mask_in[(size_t)b * a.block + i] != 0 : true);
-      const unsigned long long bal = __ballot(bit);
-      const int rank = cnt + __popcll(bal & ((1ull << tid) - 1ull));
-      if (bit && rank == m) pos = i;
-      cnt += __popcll(bal);
-    }
-    pos = wave_max_int(pos);
-    if (tid == 0) { s_pos = pos; s_cnt = cnt; }
+  int cnt = 0, pos = -1;
+  for (int base = 0; base < a.block; base += kWave) {
+    const int i = base + lane;
+    const bool bit = i < a.block && (a.mask_in ? a.mask_in[(size_t)b * a.block + i] != 0 : true);
+    const unsigned long long bal = __ballot(bit);
+    const int rank = cnt + __popcll(bal & ((1ull << lane) - 1ull));
+    if (bit && rank == m) pos = i;
+    cnt += __popcll(bal);
   }
-  __syncthreads();
-  const int pos = s_pos;
-  const int window = min(a.K, s_cnt);
-  if (tid == 0) {
+  pos = wave_max_int(pos);
+  const int window = min(a.K, cnt);
+  if (lane == 0) {
     a.slot_pos[s] = pos;
     if (m == 0) a.window[b] = window;
   }
-  if (m >= window) {
-    if (tid == 0) {
-      a.xdraft[s] = -1;
-      if (a.diag_draft_tokens) a.diag_draft_tokens[s] = -1;
+  int x = -1;
+  if (m < window) {
+    if (a.draft_tokens_in) {
+      x = min(max(a.draft_tokens_in[s], 0), a.V - 1);  // keep the gathers in bounds
+    } else {
+      // x~ = min{v : sum_{w<=v} rho_w >= u}: first over vocabulary tiles, then inside the tile
+      const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)pos, a.step,
+                                     a.seq_base + (uint32_t)b, kStreamDraft);
+      const Found tile = wave_find_first(
+          a.nT, [&](int t) { const float2 p = P[t]; return p.y * expf(p.x - lse); }, u);
+      const float* L = a.logits + (size_t)r * a.ldl;
+      const int v0 = tile_start(a, tile.idx);
+      const int nv = min(tile_start(a, tile.idx + 1), a.V) - v0;
+      const Found in = wave_find_first(
+          nv, [&](int i) { return expf(L[v0 + i] - lse); }, u - tile.before);
+      x = v0 + in.idx;
     }
-    return;
   }
-
-  int x;
-  if (a.draft_tokens_in) {
-    x = min(max(a.draft_tokens_in[s], 0), a.V - 1);  // keep the gathers in bounds
-  } else {
-    // x~ = min{v : sum_{w<=v} rho_w >= u}: first over vocabulary tiles, then inside the tile
-    const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)pos, a.step,
-                                   a.seq_base + (uint32_t)b, kStreamDraft);
-    const Found tile = block_find_first(
-        a.nT, [&](int t) { const float2 p = P[t]; return p.y * expf(p.x - lse); }, u, tmp);
-    const float* L = a.logits + (size_t)r * a.ldl;
-    const int v0 = tile.idx * a.tn;
-    const int nv = min(a.tn, a.V - v0);
-    const Found in = block_find_first(
-        nv, [&](int i) { return expf(L[v0 + i] - lse); }, u - tile.before, tmp);
-    x = v0 + in.idx;
-  }
-  if (tid == 0) {
+  if (lane == 0) {
     a.xdraft[s] = x;
     if (a.diag_draft_tokens) a.diag_draft_tokens[s] = x;
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Kernel 2: accept tests, first rejection, residual / overlap mass per chunk.
-// grid = (nslots, ceil(nRC / NW)); nslots = B (rejected slot only) or B*K (every slot).
+// Final phase for one sequence, run by the workgroup that took the sequence's last ticket.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(NT) void accept_resid_kernel(VerifyArgs a) {
-  __shared__ int s_a;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int BK = a.B * a.K;
-  const int y = blockIdx.x;            // slot (or sequence) index
-  const int cg = blockIdx.y;           // chunk group
-  const int b = a.all_slots ? y / a.K : y;
-  const int window = a.window[b];
+struct SeqState {
+  int window, acc_len;
+  int x[kMaxK];       // draft tokens of the window
+  float ptok[kMaxK];  // pi(x~)
+};
 
-  if (wave == 0) {
-    bool rejected = false;
-    float pt = 0.f;
-    if (lane < window) {
-      const int s = b * a.K + lane;
-      const int x = a.xdraft[s];
-      const float lq = a.logits[(size_t)s * a.ldl + x] - a.lse[s];
-      const float lp = a.logits[(size_t)(BK + s) * a.ldl + x] - a.lse[BK + s];
-      const float ratio = fminf(1.f, expf(lp - lq));
-      const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
-                                     a.seq_base + (uint32_t)b, kStreamAccept);
-      rejected = !(u <= ratio);
-      pt = expf(lp);
-      if (cg == 0 && (!a.all_slots || y % a.K == 0)) a.ptok[s] = pt;
-    }
-    const unsigned long long rej = __ballot(rejected);
-    const int acc_len = rej ? __ffsll((long long)rej) - 1 : window;
-    if (lane == 0) {
-      s_a = acc_len;
-      if (cg == 0 && (!a.all_slots || y % a.K == 0)) a.accept_len_ws[b] = acc_len;
-    }
-  }
-  __syncthreads();
-  const int acc_len = s_a;
-  const int m = a.all_slots ? y % a.K : acc_len;
-  if (m >= window) return;  // nothing rejected (or slot beyond the window): no masses needed
-
-  const int c = cg * NW + wave;
-  if (c >= a.nRC) return;
-  const int s = b * a.K + m;
-  const float* Lq = a.logits + (size_t)s * a.ldl;
-  const float* Lp = a.logits + (size_t)(BK + s) * a.ldl;
-  const float lse_q = a.lse[s], lse_p = a.lse[BK + s];
-  const int v = c * kResidChunk + lane * 4;
-  float4 q4 = make_float4(0.f, 0.f, 0.f, 0.f), p4 = q4;
-  if (v + 3 < a.V) {
-    q4 = *reinterpret_cast<const float4*>(Lq + v);
-    p4 = *reinterpret_cast<const float4*>(Lp + v);
-  } else {
-    float* qq = reinterpret_cast<float*>(&q4);
-    float* pp = reinterpret_cast<float*>(&p4);
-    for (int j = 0; j < 4; ++j)
-      if (v + j < a.V) { qq[j] = Lq[v + j]; pp[j] = Lp[v + j]; }
-  }
-  const float qv[4] = {q4.x, q4.y, q4.z, q4.w}, pv[4] = {p4.x, p4.y, p4.z, p4.w};
-  float rs = 0.f, as = 0.f;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    if (v + j < a.V) {
-      const float q = expf(qv[j] - lse_q), p = expf(pv[j] - lse_p);
-      rs += fmaxf(p - q, 0.f);
-      as += fminf(p, q);
-    }
-  }
-  rs = wave_sum(rs);
-  if (a.all_slots) as = wave_sum(as);
-  if (lane == 0) {
-    a.rmass[(size_t)y * a.nRC + c] = rs;
-    if (a.all_slots) a.amass[(size_t)y * a.nRC + c] = as;
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Kernel 3: residual sample, commit, mask update, LowConf.  One workgroup per sequence.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
-  __shared__ BlockTmp tmp;
-  __shared__ float s_conf[kMaxBlock];
-  __shared__ uint8_t s_mask[kMaxBlock], s_cand[kMaxBlock];
+__device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st, BlockTmp& tmp,
+                                  float* s_conf, uint8_t* s_mask, uint8_t* s_cand) {
   const int tid = threadIdx.x;
-  const int b = blockIdx.x;
   const int BK = a.B * a.K;
-  const int window = a.window[b];
-  const int acc_len = a.accept_len_ws[b];
+  const int window = st.window, acc_len = st.acc_len;
 
   // diagnostics: overlap and residual mass of every slot
   if (a.all_slots) {
@@ -337,7 +306,10 @@ __global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
       float al = 0.f, rm = 0.f;
       if (m < window) {
         const size_t base = (size_t)(b * a.K + m) * a.nRC;
-        for (int c = tid; c < a.nRC; c += NT) { al += a.amass[base + c]; rm += a.rmass[base + c]; }
+        for (int c = tid; c < a.nRC; c += NT) {
+          al += coherent_load(a.amass + base + c);
+          rm += coherent_load(a.rmass + base + c);
+        }
         al = block_sum(al, tmp);
         rm = block_sum(rm, tmp);
       }
@@ -364,13 +336,12 @@ __global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
       const int per = (a.nRC + NT - 1) / NT;
       const int begin = min(a.nRC, tid * per), end = min(a.nRC, begin + per);
       float local = 0.f;
-      for (int c = begin; c < end; ++c) local += rm[c];
+      for (int c = begin; c < end; ++c) local += coherent_load(rm + c);
       block_exclusive_scan(local, tmp, Z);
-      __syncthreads();
     }
     if (Z > 0.f) {
       const float target = u * Z;
-      const Found chunk = block_find_first(a.nRC, [&](int c) { return rm[c]; }, target, tmp);
+      const Found chunk = block_find_first(a.nRC, [&](int c) { return coherent_load(rm + c); }, target, tmp);
       const int v0 = chunk.idx * kResidChunk;
       const int nv = min(kResidChunk, a.V - v0);
       const Found in = block_find_first(
@@ -400,7 +371,7 @@ __global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
     const int s = b * a.K + tid;
     int tok = -1;
     float c = 0.f;
-    if (tid < acc_len) { tok = a.xdraft[s]; c = a.ptok[s]; }
+    if (tid < acc_len) { tok = st.x[tid]; c = st.ptok[tid]; }
     else if (tid == acc_len && acc_len < window) { tok = z; c = z_conf; }
     a.out_tokens[s] = tok;
     if (a.diag_conf_tok) a.diag_conf_tok[s] = c;
@@ -416,11 +387,10 @@ __global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
   }
   __syncthreads();
   if (tid < committed) {
-    const int s = b * a.K + tid;
-    const int pos = a.slot_pos[s];
+    const int pos = a.slot_pos[b * a.K + tid];
     s_mask[pos] = 0;
     s_cand[pos] = 1;
-    s_conf[pos] = (tid < acc_len) ? a.ptok[s] : z_conf;
+    s_conf[pos] = (tid < acc_len) ? st.ptok[tid] : z_conf;
   }
   __syncthreads();
   int unresolved = 0;
@@ -452,6 +422,93 @@ __global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Kernel 2: accept tests, first rejection, residual / overlap mass per chunk, final phase.
+// grid = (nslots, ceil(nRC / NW)); nslots = B (rejected slot only) or B*K (every slot).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void accept_resid_kernel(VerifyArgs a) {
+  __shared__ BlockTmp tmp;
+  __shared__ SeqState st;
+  __shared__ int s_last;
+  __shared__ float s_conf[kMaxBlock];
+  __shared__ uint8_t s_mask[kMaxBlock], s_cand[kMaxBlock];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int BK = a.B * a.K;
+  const int y = blockIdx.x;   // slot (all_slots) or sequence index
+  const int cg = blockIdx.y;  // chunk group
+  const int b = a.all_slots ? y / a.K : y;
+  const int window = a.window[b];
+
+  if (wave == 0) {
+    bool rejected = false;
+    if (lane < window) {
+      const int s = b * a.K + lane;
+      const int x = a.xdraft[s];
+      const float lq = a.logits[(size_t)s * a.ldl + x] - a.lse[s];
+      const float lp = a.logits[(size_t)(BK + s) * a.ldl + x] - a.lse[BK + s];
+      const float ratio = fminf(1.f, expf(lp - lq));
+      const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
+                                     a.seq_base + (uint32_t)b, kStreamAccept);
+      rejected = !(u <= ratio);
+      st.x[lane] = x;
+      st.ptok[lane] = expf(lp);
+    }
+    const unsigned long long rej = __ballot(rejected);
+    if (lane == 0) {
+      st.window = window;
+      st.acc_len = rej ? __ffsll((long long)rej) - 1 : window;
+    }
+  }
+  __syncthreads();
+  const int acc_len = st.acc_len;
+  const int m = a.all_slots ? y % a.K : acc_len;
+  const int c = cg * NW + wave;
+  if (m < window && c < a.nRC) {  // otherwise nothing was rejected / slot beyond the window
+    const int s = b * a.K + m;
+    const float* Lq = a.logits + (size_t)s * a.ldl;
+    const float* Lp = a.logits + (size_t)(BK + s) * a.ldl;
+    const float lse_q = a.lse[s], lse_p = a.lse[BK + s];
+    const int v = c * kResidChunk + lane * 4;
+    float qv[4] = {0.f, 0.f, 0.f, 0.f}, pv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (v + 3 < a.V) {
+      const float4 q4 = *reinterpret_cast<const float4*>(Lq + v);
+      const float4 p4 = *reinterpret_cast<const float4*>(Lp + v);
+      qv[0] = q4.x; qv[1] = q4.y; qv[2] = q4.z; qv[3] = q4.w;
+      pv[0] = p4.x; pv[1] = p4.y; pv[2] = p4.z; pv[3] = p4.w;
+    } else {
+      for (int j = 0; j < 4; ++j)
+        if (v + j < a.V) { qv[j] = Lq[v + j]; pv[j] = Lp[v + j]; }
+    }
+    float rs = 0.f, as = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (v + j < a.V) {
+        const float q = expf(qv[j] - lse_q), p = expf(pv[j] - lse_p);
+        rs += fmaxf(p - q, 0.f);
+        as += fminf(p, q);
+      }
+    }
+    rs = wave_sum(rs);
+    if (a.all_slots) as = wave_sum(as);
+    if (lane == 0) {
+      a.rmass[(size_t)y * a.nRC + c] = rs;
+      if (a.all_slots) a.amass[(size_t)y * a.nRC + c] = as;
+    }
+  }
+
+  // ticket: the workgroup that completes the sequence runs the final phase
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();
+    const int total = (int)gridDim.y * (a.all_slots ? a.K : 1);
+    s_last = atomicAdd(&a.counters[b], 1) == total - 1;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  finalize_sequence(a, b, st, tmp, s_conf, s_mask, s_cand);
+}
+
 __global__ void copy_logits_kernel(const float* __restrict__ src, long ldl, float* __restrict__ dst,
                                    int V, long rows) {
   const long n = rows * V;
@@ -465,11 +522,10 @@ __global__ void copy_logits_kernel(const float* __restrict__ src, long ldl, floa
 
 hipError_t launch_verify(const VerifyArgs& a) {
   const int M = 2 * a.B * a.K;
-  hipLaunchKernelGGL(row_lse_draft_kernel, dim3(M), dim3(NT), 0, a.stream, a);
+  hipLaunchKernelGGL(row_lse_draft_kernel, dim3((M + NW - 1) / NW), dim3(NT), 0, a.stream, a);
   const int gx = (a.nRC + NW - 1) / NW;
   const int nslots = a.all_slots ? a.B * a.K : a.B;
   hipLaunchKernelGGL(accept_resid_kernel, dim3(nslots, gx), dim3(NT), 0, a.stream, a);
-  hipLaunchKernelGGL(finalize_kernel, dim3(a.B), dim3(NT), 0, a.stream, a);
   if (a.diag_logits) {
     const long rows = M;
     const long n = rows * a.V;

@@ -2,9 +2,10 @@
 
 Discrete outputs (tokens, accepted length, re-mask set) must be bit-exact.  The one exception
 is a decision that floating point cannot separate: the oracle reports, per slot, how far each
-uniform was from the boundary it was compared with, and a sequence whose outcome hinges on a
-boundary closer than the tolerances below is counted as near-margin and left out of the exact
-comparison (a flipped decision changes everything after it).  Tolerances:
+uniform was from the boundary it was compared with.  A sequence whose outcome hinges on a
+boundary closer than the tolerances below is counted as near-margin; it is still compared, and
+only there may the two sides differ (a flipped decision changes everything after it) - such
+flips are counted separately.  Tolerances:
 
   accept test     |u - min(1, p/q)| < 1e-4     (fp32 log-ratio of four logits/lse terms)
   inverse CDFs    gap to the nearest CDF edge < 1e-5 (relative to the residual mass for the
@@ -28,8 +29,8 @@ def compare(ref, tokens, accept_len, remask, diag=None, drafts_given=False, logi
     """ref: oracle StepResult; tokens/accept_len/remask: numpy arrays from the HIP path;
     diag: dict of numpy arrays (optional).  Returns counters; raises AssertionError on mismatch."""
     B, K = ref.tokens.shape
-    stats = {"sequences": B, "near_margin": 0, "compared": 0, "remask_skipped": 0,
-             "draft_slots": 0, "draft_near": 0}
+    stats = {"sequences": B, "equal": 0, "near_margin": 0, "near_flipped": 0, "compared": 0,
+             "remask_skipped": 0, "draft_slots": 0, "draft_near": 0}
     for b in range(B):
         w, a = int(ref.window[b]), int(ref.accept_len[b])
         last = min(a, w - 1)
@@ -41,16 +42,19 @@ def compare(ref, tokens, accept_len, remask, diag=None, drafts_given=False, logi
                 near = True
         if a < w and ref.resid_gap[b] < TOL_CDF:
             near = True
-        if near:
-            stats["near_margin"] += 1
+        near_remask = ref.lowconf_gap[b] < TOL_CONF
+        same = int(accept_len[b]) == a and np.array_equal(tokens[b], ref.tokens[b])
+        same_remask = np.array_equal(remask[b], ref.remask[b])
+        stats["near_margin"] += int(near)
+        stats["compared"] += int(not near)
+        if same and (same_remask or near_remask):
+            stats["equal"] += 1
+            stats["remask_skipped"] += int(not same_remask)
             continue
-        stats["compared"] += 1
-        assert int(accept_len[b]) == a, f"seq {b}: accept_len {accept_len[b]} != {a}"
-        assert np.array_equal(tokens[b], ref.tokens[b]), f"seq {b}: tokens {tokens[b]} != {ref.tokens[b]}"
-        if ref.lowconf_gap[b] < TOL_CONF:
-            stats["remask_skipped"] += 1
-        else:
-            assert np.array_equal(remask[b], ref.remask[b]), f"seq {b}: remask {remask[b]} != {ref.remask[b]}"
+        # a difference is tolerated only where the oracle says the decision was within rounding
+        assert near, (f"seq {b}: accept_len {accept_len[b]} vs {a}, tokens {tokens[b]} vs {ref.tokens[b]}, "
+                      f"remask {remask[b]} vs {ref.remask[b]}")
+        stats["near_flipped"] += 1
     if diag is not None:
         active = np.arange(K)[None, :] < ref.window[:, None]
         if "draft_tokens" in diag and not drafts_given:
