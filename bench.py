@@ -52,12 +52,12 @@ class HipEvents:
         self.hip.hipEventDestroy(e)
 
 
-def head_bytes(wl, variant_tn):
+def head_bytes(wl, skinny):
     """Algorithmic HBM bytes of one vocabulary-head launch: W once, H once, fp32 logits
     written once, the per-tile (max, sum exp) partials."""
     M = 2 * wl.B * wl.K
     esz = 2 if wl.dtype == "bf16" else 4
-    nT = -(-wl.V // variant_tn)
+    nT = min(-(-wl.V // 16), 256) if skinny else -(-wl.V // 64)
     return wl.V * wl.d * esz + M * wl.d * esz + M * wl.V * 4 + M * nT * 8
 
 
@@ -93,6 +93,9 @@ def main():
     ap.add_argument("--workload", default="llada_b1")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="N",
+                    help="instead of the benchmark, run the library's plain copy kernel N times on a "
+                         "1 GiB buffer (profiler byte-counter calibration)")
     ap.add_argument("--events", choices=["inline", "separate"], default="inline",
                     help="record the head-kernel events inside the timed steps, or in a second pass")
     args = ap.parse_args()
@@ -108,6 +111,14 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_probe:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_probe):
+            fb.fef_copy_probe(dst, src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_launches": args.copy_probe, "bytes_read": 1 << 30, "bytes_written": 1 << 30}))
+        return
     W = synth.make_head(wl.V, wl.d, args.seed, wl.dtype)
     Wd = W.to(dev)
     n_rounds = 16   # distinct hidden-state batches, cycled, so only W could ever sit in a cache
@@ -116,7 +127,6 @@ def main():
 
     vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, dtype=wl.dtype, device=dev)
     variant = fb.fef_select_gemm(vs._params(), wl.K)
-    tn = 16 if variant == fb.FEF_GEMM_SKINNY else 64
     ev = HipEvents()
     pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
 
@@ -143,7 +153,7 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     positions = wl.B * wl.K
     M = 2 * positions
-    hb = head_bytes(wl, tn)
+    hb = head_bytes(wl, variant == fb.FEF_GEMM_SKINNY)
     flops = 2.0 * M * wl.V * wl.d
     hbm_time, mfma_time = hb / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if hbm_time >= mfma_time:

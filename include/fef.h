@@ -103,8 +103,8 @@ typedef struct {
   void* workspace;             /* device scratch, 256-byte aligned                           */
   size_t workspace_bytes;
   void* stream;                /* hipStream_t; NULL = the null stream                        */
-  void* ev_head_begin;         /* optional hipEvent_t recorded on `stream` right before ...  */
-  void* ev_head_end;           /* ... and right after the vocabulary-head kernel (profiling) */
+  void* ev_head_begin;         /* optional hipEvent_t pair (both or neither) that receives    */
+  void* ev_head_end;           /* the vocabulary-head kernel's own start / stop timestamps    */
 } fef_params;
 
 /* Bytes of device workspace a call with these sizes needs (depends on B, d, V, dtype,
@@ -137,6 +137,12 @@ int32_t fef_select_gemm(const fef_params* prm, int32_t K);
  * use; lets callers and tests reproduce a draw.  Pure host function. */
 float fef_uniform(uint64_t seed, uint32_t position, uint32_t step, uint32_t sequence,
                   uint32_t stream);
+
+/* Measurement aid, not part of the verify path: copy nbytes (a multiple of 16) from src to dst
+ * (both device, 16-byte aligned, not overlapping) with a plain streaming kernel of known HBM
+ * traffic (nbytes read + nbytes written).  Profiler byte counters are scaled by what they
+ * report for this kernel.  Asynchronous on `stream` (hipStream_t, NULL = null stream). */
+fef_status fef_copy_probe(void* dst, const void* src, size_t nbytes, void* stream);
 
 const char* fef_status_string(fef_status s);
 const char* fef_last_error(void);

@@ -8,7 +8,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfef.so")
+LIB_PATH = os.environ.get("FEF_LIB") or os.path.join(_HERE, "libfef.so")  # FEF_LIB: another build of the same library
 
 FEF_OK = 0
 FEF_ERR_INVALID_ARG = -1
@@ -20,7 +20,7 @@ FEF_GEMM_AUTO, FEF_GEMM_SKINNY, FEF_GEMM_TILED, FEF_GEMM_F32 = 0, 1, 2, 3
 FEF_MAX_K, FEF_MAX_BLOCK = 64, 4096
 
 EXPORTS = ["fef_workspace_bytes", "fef_verify_step", "fef_select_gemm", "fef_uniform",
-           "fef_status_string", "fef_last_error", "fef_abi_version"]
+           "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe"]
 
 
 class fef_params(ctypes.Structure):
@@ -76,6 +76,8 @@ def lib():
         L.fef_status_string.argtypes = [ctypes.c_int]
         L.fef_last_error.restype = ctypes.c_char_p
         L.fef_last_error.argtypes = []
+        L.fef_copy_probe.restype = ctypes.c_int
+        L.fef_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.fef_abi_version.restype = ctypes.c_int32
         L.fef_abi_version.argtypes = []
         _lib = L
@@ -122,6 +124,15 @@ def fef_verify_step(params, h_draft, h_target, W_vocab, K, block, seed, out_toke
     if s != FEF_OK:
         raise FefError(s, fef_last_error())
     return s
+
+
+def fef_copy_probe(dst, src):
+    """Plain device copy of known traffic (profiler counter calibration)."""
+    assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
+    s = lib().fef_copy_probe(_ptr(dst), _ptr(src), src.numel() * src.element_size(),
+                             ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if s != FEF_OK:
+        raise FefError(s, fef_last_error())
 
 
 class VerifyStep:

@@ -114,9 +114,25 @@ fef_status make_layout(const fef_params* p, int32_t K, int32_t block, Layout* L)
   return FEF_OK;
 }
 
+__global__ __launch_bounds__(256) void copy_probe_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                        size_t n16) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
 }  // namespace
 
 extern "C" {
+
+fef_status fef_copy_probe(void* dst, const void* src, size_t nbytes, void* stream) {
+  if (!dst || !src || nbytes == 0 || nbytes % 16 || (((uintptr_t)dst | (uintptr_t)src) & 15))
+    return fail(FEF_ERR_INVALID_ARG, "copy probe needs non-NULL 16-byte aligned pointers and a size multiple of 16");
+  hipLaunchKernelGGL(copy_probe_kernel, dim3(2048), dim3(256), 0, (hipStream_t)stream, (uint4*)dst,
+                     (const uint4*)src, nbytes / 16);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FEF_ERR_HIP, "copy probe launch: %s", hipGetErrorString(e));
+  return FEF_OK;
+}
 
 size_t fef_workspace_bytes(const fef_params* prm, int32_t K, int32_t block) {
   Layout L;
@@ -144,6 +160,8 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
     return fail(FEF_ERR_INVALID_ARG, "out_tokens, out_accept_len and out_remask must not be NULL");
   if (((uintptr_t)h_draft | (uintptr_t)h_target | (uintptr_t)W_vocab) & 15)
     return fail(FEF_ERR_INVALID_ARG, "h_draft, h_target and W_vocab must be 16-byte aligned");
+  if (!prm->ev_head_begin != !prm->ev_head_end)
+    return fail(FEF_ERR_INVALID_ARG, "ev_head_begin and ev_head_end must be given together");
   if (!prm->workspace) return fail(FEF_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", L.total);
   if ((uintptr_t)prm->workspace & 255) return fail(FEF_ERR_WORKSPACE, "workspace must be 256-byte aligned");
   if (prm->workspace_bytes < L.total)
@@ -159,17 +177,14 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   h.logits = (float*)(ws + L.off_logits); h.ldl = L.ldl;
   h.partials = (float2*)(ws + L.off_partials); h.nT = L.nT;
   h.stream = stream;
+  h.ev_begin = (hipEvent_t)prm->ev_head_begin; h.ev_end = (hipEvent_t)prm->ev_head_end;
   hipError_t e;
-  if (prm->ev_head_begin && (e = hipEventRecord((hipEvent_t)prm->ev_head_begin, stream)) != hipSuccess)
-    return fail(FEF_ERR_HIP, "hipEventRecord: %s", hipGetErrorString(e));
   switch (L.variant) {
     case FEF_GEMM_SKINNY: e = fef::launch_head_skinny(h); break;
     case FEF_GEMM_TILED: e = fef::launch_head_tiled(h); break;
     default: e = fef::launch_head_f32(h); break;
   }
   if (e != hipSuccess) return fail(FEF_ERR_HIP, "head kernel launch: %s", hipGetErrorString(e));
-  if (prm->ev_head_end && (e = hipEventRecord((hipEvent_t)prm->ev_head_end, stream)) != hipSuccess)
-    return fail(FEF_ERR_HIP, "hipEventRecord: %s", hipGetErrorString(e));
 
   fef::VerifyArgs v;
   memset(&v, 0, sizeof v);

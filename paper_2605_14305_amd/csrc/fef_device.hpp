@@ -55,8 +55,9 @@ struct HeadArgs {
   float* logits;         // [2*BK, ldl]
   long ldl;
   float2* partials;      // [2*BK, nT]
-  int nT;                // ceil(V / tn)
+  int nT;                // partial tiles per row
   hipStream_t stream;
+  hipEvent_t ev_begin, ev_end;  // optional: receive the kernel's own start / stop timestamps
 };
 
 constexpr int kSkinnyUnit = 16;     // the skinny kernel walks W in tiles of 16 tokens ...

@@ -14,6 +14,7 @@
 //   head_tiled_kernel   any M.  128x128x64 LDS-tiled MFMA GEMM, XCD-aware tile order so the
 //                       workgroups that share a W tile run on the same L2.
 //   head_f32_kernel     fp32 inputs, plain FMA; tiny instances only.
+#include <hip/hip_ext.h>
 #include <math.h>
 
 #include "fef_device.hpp"
@@ -43,11 +44,18 @@ __device__ inline const __bf16* h_row(const HeadArgs& a, int r) {
 //   D (16 x 16): lane holds D[4g + r][i], r = 0..3  -> logits of 4 consecutive tokens, row i
 // ---------------------------------------------------------------------------------------------
 constexpr int kSkinnyWaves = 8;
+constexpr int kSkinnyOutTiles = 40;  // tiles of logits staged in LDS before a flush
 constexpr int kSkinnyThreads = kSkinnyWaves * kWave;
 
-template <int KS>
+// NB = tiles accumulated in registers between two cross-wavefront reductions (even).
+template <int KS, int NB>
 __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a, int tiles_total) {
-  __shared__ floatx4 red[2][kSkinnyWaves][kWave];
+  __shared__ floatx4 red[2][NB][kSkinnyWaves][kWave];
+  __shared__ float2 run_merge[kSkinnyThreads / 16];
+  // Logits of this workgroup's tokens wait here and leave in one coalesced burst: a global
+  // store inside the streaming loop would share the vector-memory counter with the W
+  // prefetch and force every wait on a W tile to drain the tiles fetched ahead as well.
+  __shared__ float out[16][kSkinnyOutTiles * 16 + 4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, g = lane >> 4;
   const int M = 2 * a.BK;
@@ -75,51 +83,89 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
 #pragma unroll
     for (int s = 0; s < KS; ++s) buf[s] = *reinterpret_cast<const bf16x8*>(wp + 32 * s);
   };
-
-  auto compute_tile = [&](int t, const bf16x8(&buf)[KS], int par, float& run_m, float& run_s) {
+  auto mfma_tile = [&](const bf16x8(&buf)[KS]) {
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s)
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[s], hreg[s], acc, 0, 0, 0);
-    red[par][wave][lane] = acc;
-    lds_barrier();
-    if (tid < 256) {
-      // thread -> (row m, token vl) of the 16x16 tile; sum the eight k-slices in wave order
-      const int m = tid >> 4, vl = tid & 15;
-      const int src = m + 16 * (vl >> 2), comp = vl & 3;
-      float sum = 0.f;
-#pragma unroll
-      for (int w = 0; w < kSkinnyWaves; ++w) sum += red[par][w][src][comp];
-      const float logit = sum * a.inv_tau;
-      const int v = t * 16 + vl;
-      const bool valid = v < a.V && m < M;
-      if (valid) a.logits[(size_t)m * a.ldl + v] = logit;
-      float mx = valid ? logit : -INFINITY;
-#pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-      float e = valid ? __expf(logit - mx) : 0.f;
-#pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) e += __shfl_xor(e, off, 64);
-      if (mx > run_m) { run_s = run_s * __expf(run_m - mx) + e; run_m = mx; }
-      else if (mx > -INFINITY) run_s += e * __expf(mx - run_m);
-    }
+    return acc;
   };
 
-  // running (max, sum exp) of this workgroup's tokens, per row, replicated over the row's 16 lanes
+  // Output element of this thread inside a batch: row m, token vl of tile (tid >> 8) + 2 q.
+  const int m = (tid >> 4) & 15, vl = tid & 15;
+  const int src = m + 16 * (vl >> 2), comp = vl & 3;
+  // running (max, sum exp) over this thread's tiles, replicated over the row's 16 lanes
   float run_m = -INFINITY, run_s = 0.f;
 
   bf16x8 buf0[KS], buf1[KS];
+  floatx4 acc[NB];
+  int par = 0;
+  int tflush = t0;  // first tile whose logits are still staged in LDS
   if (t0 < t1) load_tile(t0, buf0);
-  for (int t = t0; t < t1; t += 2) {
-    if (t + 1 < t1) load_tile(t + 1, buf1);
-    compute_tile(t, buf0, 0, run_m, run_s);
-    if (t + 1 < t1) {
-      if (t + 2 < t1) load_tile(t + 2, buf0);
-      compute_tile(t + 1, buf1, 1, run_m, run_s);
+  for (int t = t0; t < t1; t += NB) {
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      if (t + i < t1) {
+        if (i & 1) {
+          if (t + i + 1 < t1) load_tile(t + i + 1, buf0);
+          acc[i] = mfma_tile(buf1);
+        } else {
+          if (t + i + 1 < t1) load_tile(t + i + 1, buf1);
+          acc[i] = mfma_tile(buf0);
+        }
+      }
+    }
+    const int nb = min(NB, t1 - t);
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      if (i < nb) red[par][i][wave][lane] = acc[i];
+    lds_barrier();
+    // sum the eight k-slices in wave order; 512 threads cover two tiles per pass
+#pragma unroll
+    for (int q = 0; q < NB / 2; ++q) {
+      const int jt = (tid >> 8) + 2 * q;
+      if (jt < nb) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kSkinnyWaves; ++w) sum += red[par][jt][w][src][comp];
+        const float logit = sum * a.inv_tau;
+        const int v = (t + jt) * 16 + vl;
+        const bool valid = v < a.V && m < M;
+        out[m][(t + jt - tflush) * 16 + vl] = logit;
+        float mx = valid ? logit : -INFINITY;
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+        float e = valid ? __expf(logit - mx) : 0.f;
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) e += __shfl_xor(e, off, 64);
+        if (mx > run_m) { run_s = run_s * __expf(run_m - mx) + e; run_m = mx; }
+        else if (mx > -INFINITY) run_s += e * __expf(mx - run_m);
+      }
+    }
+    par ^= 1;
+    if (t + NB - tflush + NB > kSkinnyOutTiles || t + NB >= t1) {
+      // flush rows [tflush*16, min(t+NB, t1)*16) of the staged logits
+      const int tend = min(t + NB, t1);
+      const int v0 = tflush * 16, nv = min(tend * 16, a.V) - v0;
+      __syncthreads();
+      for (int r = wave; r < M; r += kSkinnyWaves)
+        for (int i = lane; i < nv; i += kWave) a.logits[(size_t)r * a.ldl + v0 + i] = out[r][i];
+      __syncthreads();
+      tflush = tend;
     }
   }
-  if (tid < 256 && (tid & 15) == 0 && (tid >> 4) < M)
-    a.partials[(size_t)(tid >> 4) * a.nT + blockIdx.x] = make_float2(run_m, run_s);
+
+  // merge the two threads that share a row (tid and tid + 256) and write the workgroup's partial
+  if (vl == 0) run_merge[tid >> 4] = make_float2(run_m, run_s);
+  __syncthreads();
+  if (tid < 16 && tid < M) {
+    const float2 p0 = run_merge[tid], p1 = run_merge[tid + 16];
+    const float mx = fmaxf(p0.x, p1.x);
+    float sm = 0.f;
+    if (p0.x > -INFINITY) sm += p0.y * __expf(p0.x - mx);
+    if (p1.x > -INFINITY) sm += p1.y * __expf(p1.x - mx);
+    a.partials[(size_t)tid * a.nT + blockIdx.x] = make_float2(mx, sm);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -259,18 +305,22 @@ __global__ __launch_bounds__(kWave) void head_f32_kernel(HeadArgs a) {
 
 bool skinny_supports(int M, int d) { return M <= 16 && (d == 512 || d == 3584 || d == 4096); }
 
-hipError_t launch_head_skinny(const HeadArgs& a) {
+template <int NB>
+hipError_t launch_head_skinny_nb(const HeadArgs& a) {
   const int tiles = (a.V + kSkinnyUnit - 1) / kSkinnyUnit;
   const int grid = a.nT;  // = min(tiles, kSkinnyMaxGrid): one partial per (row, workgroup)
   switch (a.d) {
     case 512:
-      hipLaunchKernelGGL(head_skinny_kernel<2>, dim3(grid), dim3(kSkinnyThreads), 0, a.stream, a, tiles);
+      hipExtLaunchKernelGGL((head_skinny_kernel<2, NB>), dim3(grid), dim3(kSkinnyThreads), 0, a.stream,
+                            a.ev_begin, a.ev_end, 0, a, tiles);
       break;
     case 3584:
-      hipLaunchKernelGGL(head_skinny_kernel<14>, dim3(grid), dim3(kSkinnyThreads), 0, a.stream, a, tiles);
+      hipExtLaunchKernelGGL((head_skinny_kernel<14, NB>), dim3(grid), dim3(kSkinnyThreads), 0, a.stream,
+                            a.ev_begin, a.ev_end, 0, a, tiles);
       break;
     case 4096:
-      hipLaunchKernelGGL(head_skinny_kernel<16>, dim3(grid), dim3(kSkinnyThreads), 0, a.stream, a, tiles);
+      hipExtLaunchKernelGGL((head_skinny_kernel<16, NB>), dim3(grid), dim3(kSkinnyThreads), 0, a.stream,
+                            a.ev_begin, a.ev_end, 0, a, tiles);
       break;
     default:
       return hipErrorInvalidValue;
@@ -278,17 +328,20 @@ hipError_t launch_head_skinny(const HeadArgs& a) {
   return hipGetLastError();
 }
 
+hipError_t launch_head_skinny(const HeadArgs& a) { return launch_head_skinny_nb<4>(a); }
+
 hipError_t launch_head_tiled(const HeadArgs& a) {
   const int M = 2 * a.BK;
   const int m_tiles = (M + TM - 1) / TM, n_tiles = (a.V + TN - 1) / TN;
   const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
-  hipLaunchKernelGGL(head_tiled_kernel, dim3((unsigned)grid), dim3(kTiledThreads), 0, a.stream, a,
-                     m_tiles, n_tiles);
+  hipExtLaunchKernelGGL(head_tiled_kernel, dim3((unsigned)grid), dim3(kTiledThreads), 0, a.stream,
+                        a.ev_begin, a.ev_end, 0, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 
 hipError_t launch_head_f32(const HeadArgs& a) {
-  hipLaunchKernelGGL(head_f32_kernel, dim3(a.nT, 2 * a.BK), dim3(kWave), 0, a.stream, a);
+  hipExtLaunchKernelGGL(head_f32_kernel, dim3(a.nT, 2 * a.BK), dim3(kWave), 0, a.stream, a.ev_begin,
+                        a.ev_end, 0, a);
   return hipGetLastError();
 }
 
