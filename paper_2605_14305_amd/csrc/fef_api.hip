@@ -59,7 +59,8 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
   int v = p->gemm_variant;
   if (v == FEF_GEMM_AUTO) {
     if (p->dtype == FEF_F32) v = FEF_GEMM_F32;
-    else v = fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d) ? FEF_GEMM_SKINNY : FEF_GEMM_TILED;
+    else if (fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d)) v = FEF_GEMM_SKINNY;
+    else v = M > 128 ? FEF_GEMM_TILED256 : FEF_GEMM_TILED;
   }
   switch (v) {
     case FEF_GEMM_SKINNY:
@@ -67,7 +68,8 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
         return fail(FEF_ERR_UNSUPPORTED, "skinny head kernel needs bf16, 2*B*K <= 16 and d in {512, 3584, 4096}");
       break;
     case FEF_GEMM_TILED:
-      if (p->dtype != FEF_BF16) return fail(FEF_ERR_UNSUPPORTED, "tiled head kernel is bf16 only");
+    case FEF_GEMM_TILED256:
+      if (p->dtype != FEF_BF16) return fail(FEF_ERR_UNSUPPORTED, "tiled head kernels are bf16 only");
       break;
     case FEF_GEMM_F32:
       if (p->dtype != FEF_F32) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel needs dtype f32");
@@ -182,6 +184,7 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   switch (L.variant) {
     case FEF_GEMM_SKINNY: e = fef::launch_head_skinny(h); break;
     case FEF_GEMM_TILED: e = fef::launch_head_tiled(h); break;
+    case FEF_GEMM_TILED256: e = fef::launch_head_tiled256(h); break;
     default: e = fef::launch_head_f32(h); break;
   }
   if (e != hipSuccess) return fail(FEF_ERR_HIP, "head kernel launch: %s", hipGetErrorString(e));

@@ -68,6 +68,7 @@ constexpr int kTiledTn = 64;         // partial-tile width of the tiled and f32 
 bool skinny_supports(int M, int d);
 hipError_t launch_head_skinny(const HeadArgs& a);
 hipError_t launch_head_tiled(const HeadArgs& a);
+hipError_t launch_head_tiled256(const HeadArgs& a);
 hipError_t launch_head_f32(const HeadArgs& a);
 
 // ---------------------------------------------------------------------------------------------

@@ -1,0 +1,48 @@
+// Internal helpers shared by the vocabulary-head kernels.
+#pragma once
+#include <hip/hip_ext.h>
+#include <math.h>
+
+#include "fef_device.hpp"
+
+namespace fef {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Workgroup barrier that waits for this wavefront's LDS traffic only.  __syncthreads() would
+// also drain the vector-memory counter and with it the W tiles prefetched for later steps.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+__device__ inline const __bf16* h_row(const HeadArgs& a, int r) {
+  return r < a.BK ? (const __bf16*)a.h_draft + (size_t)r * a.d
+                  : (const __bf16*)a.h_target + (size_t)(r - a.BK) * a.d;
+}
+
+// LDS tiles of bf16 are [rows][64 k] = 128 B per row.  The LDS has 64 four-byte banks, so two
+// consecutive rows cover all banks once; the eight 16-byte chunks of a row are stored at
+// chunk ^ ((row >> 1) & 7) so that 16-byte reads of one k-chunk over 16 consecutive rows
+// touch every bank exactly once.
+#ifndef FEF_SWZ_SHIFT
+#define FEF_SWZ_SHIFT 1
+#endif
+__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ ((row >> FEF_SWZ_SHIFT) & 7)); }
+
+// DPP within rows of 16 lanes: rotate right by N lanes (row_ror:N).
+template <int N>
+__device__ inline float row_ror(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + N, 0xf, 0xf, false));
+}
+// All-reduce over the 16 lanes of a DPP row.
+__device__ inline float row16_max(float x) {
+  x = fmaxf(x, row_ror<8>(x)); x = fmaxf(x, row_ror<4>(x));
+  x = fmaxf(x, row_ror<2>(x)); x = fmaxf(x, row_ror<1>(x));
+  return x;
+}
+__device__ inline float row16_sum(float x) {
+  x += row_ror<8>(x); x += row_ror<4>(x); x += row_ror<2>(x); x += row_ror<1>(x);
+  return x;
+}
+
+}  // namespace fef

@@ -14,26 +14,10 @@
 //   head_tiled_kernel   any M.  128x128x64 LDS-tiled MFMA GEMM, XCD-aware tile order so the
 //                       workgroups that share a W tile run on the same L2.
 //   head_f32_kernel     fp32 inputs, plain FMA; tiny instances only.
-#include <hip/hip_ext.h>
-#include <math.h>
-
-#include "fef_device.hpp"
+#include "head_common.hpp"
 
 namespace fef {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-// Workgroup barrier that waits for this wavefront's LDS traffic only.  __syncthreads() would
-// also drain the vector-memory counter and with it the W tiles prefetched for later steps.
-__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-__device__ inline const __bf16* h_row(const HeadArgs& a, int r) {
-  return r < a.BK ? (const __bf16*)a.h_draft + (size_t)r * a.d
-                  : (const __bf16*)a.h_target + (size_t)(r - a.BK) * a.d;
-}
 
 // ---------------------------------------------------------------------------------------------
 // Skinny kernel.  KS = MFMA k-steps (32 wide) per wavefront; d = 8 * KS * 32.
@@ -182,8 +166,6 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
 // ---------------------------------------------------------------------------------------------
 constexpr int TM = 128, TN = 128, TK = 64;
 constexpr int kTiledThreads = 256;
-
-__device__ inline int swz(int row, int chunk) { return row * 8 + (chunk ^ (row & 7)); }
 
 __global__ __launch_bounds__(kTiledThreads) void head_tiled_kernel(HeadArgs a, int m_tiles, int n_tiles) {
   __shared__ bf16x8 As[TM * 8];

@@ -54,7 +54,8 @@ def test_gemm_selection(lib):
     assert fb.fef_select_gemm(fb.make_params(1, 4096, 126464), 8) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(1, 3584, 151936), 8) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(1, 4096, 126464), 16) == fb.FEF_GEMM_TILED
-    assert fb.fef_select_gemm(fb.make_params(16, 4096, 126464), 8) == fb.FEF_GEMM_TILED
+    assert fb.fef_select_gemm(fb.make_params(16, 4096, 126464), 8) == fb.FEF_GEMM_TILED256
+    assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_TILED
     assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_TILED
     assert fb.fef_select_gemm(fb.make_params(1, 64, 32, dtype=fb.FEF_F32), 4) == fb.FEF_GEMM_F32
     p = fb.make_params(16, 4096, 126464, gemm_variant=fb.FEF_GEMM_SKINNY)

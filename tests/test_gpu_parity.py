@@ -99,6 +99,13 @@ def test_tiled_kernel_small_shapes(B, K, d, V):
     assert st["near_flipped"] <= B // 20
 
 
+@pytest.mark.parametrize("B,K,d,V", [(5, 8, 64, 1000), (20, 8, 512, 777), (40, 4, 128, 2050), (1, 1, 64, 1),
+                                     (17, 16, 256, 300)])
+def test_tiled256_kernel_small_shapes(B, K, d, V):
+    ref, out, st = run_case(B, K, max(K, 16), d, V, seed=13, rho=0.8, variant=fb.FEF_GEMM_TILED256)
+    assert st["near_flipped"] <= B // 20
+
+
 def test_skinny_and_tiled_agree():
     W = synth.make_head(3000, 512, 5)
     hidden = synth.make_hidden(1, 8, 512, 5, 0.7, 3.0 / (0.02 * np.sqrt(512)))
@@ -112,7 +119,7 @@ def test_skinny_and_tiled_agree():
 def test_deterministic_bits():
     W = synth.make_head(5000, 512, 1).to(DEV)
     hd, ht = (t.to(DEV) for t in synth.make_hidden(2, 4, 512, 1, 0.8, 3.0 / (0.02 * np.sqrt(512))))
-    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED):
+    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED, fb.FEF_GEMM_TILED256):
         outs = []
         for rep in range(3):
             vs = fb.VerifyStep(2, 4, 8, 512, 5000, diag=True, diag_logits=True, gemm_variant=variant)
