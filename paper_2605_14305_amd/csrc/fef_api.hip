@@ -24,7 +24,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Layout {
   int variant, nT, tile_unit, tile_T, nRC, all_slots;
   long ldl;
-  size_t off_logits, off_partials, off_lse, off_xdraft, off_slot_pos, off_window, off_counters,
+  size_t off_logits, off_partials, off_lse, off_xdraft, off_slot_pos, off_window, off_seqstate,
       off_rmass, off_amass, total;
 };
 
@@ -109,7 +109,7 @@ fef_status make_layout(const fef_params* p, int32_t K, int32_t block, Layout* L)
   L->off_xdraft = take(BK * sizeof(int32_t));
   L->off_slot_pos = take(BK * sizeof(int32_t));
   L->off_window = take((size_t)p->B * sizeof(int32_t));
-  L->off_counters = take((size_t)p->B * sizeof(int32_t));
+  L->off_seqstate = take((size_t)p->B * sizeof(fef::SeqState));
   L->off_rmass = take(nslots * (size_t)L->nRC * sizeof(float));
   L->off_amass = take(L->all_slots ? nslots * (size_t)L->nRC * sizeof(float) : 0);
   L->total = o;
@@ -202,7 +202,7 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   v.xdraft = (int32_t*)(ws + L.off_xdraft);
   v.slot_pos = (int32_t*)(ws + L.off_slot_pos);
   v.window = (int32_t*)(ws + L.off_window);
-  v.counters = (int32_t*)(ws + L.off_counters);
+  v.seqstate = (fef::SeqState*)(ws + L.off_seqstate);
   v.rmass = (float*)(ws + L.off_rmass);
   v.amass = (float*)(ws + L.off_amass);
   v.nRC = L.nRC; v.all_slots = L.all_slots;

@@ -76,6 +76,12 @@ hipError_t launch_head_f32(const HeadArgs& a);
 // ---------------------------------------------------------------------------------------------
 constexpr int kResidChunk = 256;  // vocabulary entries per residual-mass chunk
 
+struct SeqState {
+  int window, acc_len;
+  int x[kMaxK];       // draft tokens of the window
+  float ptok[kMaxK];  // pi(x~)
+};
+
 struct VerifyArgs {
   int B, K, block, V;
   long ldl;
@@ -95,7 +101,7 @@ struct VerifyArgs {
   int32_t* xdraft;          // [B*K]
   int32_t* slot_pos;        // [B*K]
   int32_t* window;          // [B]
-  int32_t* counters;        // [B] completion tickets of accept_resid_kernel
+  struct SeqState* seqstate;  // [B] accept-phase results handed to the final kernel
   float* rmass;             // [nslots, nRC] residual mass per chunk
   float* amass;             // [nslots, nRC] overlap mass per chunk (all_slots only)
   int nRC;                  // ceil(V / kResidChunk)
