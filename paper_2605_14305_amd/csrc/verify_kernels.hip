@@ -22,33 +22,13 @@
 #include <math.h>
 
 #include "fef_device.hpp"
+#include "wave_ops.hpp"
 
 namespace fef {
 namespace {
 
 constexpr int NT = 256;          // threads per workgroup of every kernel in this file
 constexpr int NW = NT / kWave;   // wavefronts per workgroup
-
-__device__ inline float wave_sum(float x) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
-  return x;
-}
-__device__ inline float wave_max(float x) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
-  return x;
-}
-__device__ inline int wave_min_int(int x) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x = min(x, __shfl_xor(x, off, 64));
-  return x;
-}
-__device__ inline int wave_max_int(int x) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x = max(x, __shfl_xor(x, off, 64));
-  return x;
-}
 
 struct BlockTmp {
   float f[NW];
@@ -101,12 +81,7 @@ __device__ inline int block_max_int(int x, BlockTmp& t) {
 // Exclusive prefix sum of one value per thread in thread order; `total` gets the sum.
 __device__ inline float block_exclusive_scan(float x, BlockTmp& t, float& total) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  float inc = x;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const float y = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += y;
-  }
+  const float inc = wave_scan_add(x);
   float exc = __shfl_up(inc, 1, 64);
   if (lane == 0) exc = 0.f;
   __syncthreads();
@@ -178,12 +153,7 @@ __device__ inline Found wave_find_first(int n, F mass, float target) {
   const int begin = min(n, lane * per), end = min(n, begin + per);
   float local = 0.f;
   for (int i = begin; i < end; ++i) local += mass(i);
-  float inc = local;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const float y = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += y;
-  }
+  const float inc = wave_scan_add(local);
   float exc = __shfl_up(inc, 1, 64);
   if (lane == 0) exc = 0.f;
   float run = exc, before = 0.f, before_pos = 0.f;
@@ -210,37 +180,48 @@ __device__ inline Found wave_find_first(int n, F mass, float target) {
   return f;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Kernel 1: per-row log-sum-exp, window slot, draft sample.  One wavefront per row.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int BK = a.B * a.K;
-  const int r = blockIdx.x * NW + wave;
-  if (r >= 2 * BK) return;
-  const bool is_draft = r < BK;
-  const int s = is_draft ? r : r - BK;
-  const int b = s / a.K, m = s % a.K;
-
-  // log-sum-exp of the row from the head kernel's per-tile partials
-  const float2* P = a.partials + (size_t)r * a.nT;
-  float mx = -INFINITY;
-  for (int t = lane; t < a.nT; t += kWave) mx = fmaxf(mx, P[t].x);
-  mx = wave_max(mx);
-  float sm = 0.f;
-  for (int t = lane; t < a.nT; t += kWave) {
-    const float2 p = P[t];
-    sm += p.y * expf(p.x - mx);
+// Register-resident variant of wave_find_first: lane l holds the masses of elements
+// l*PER .. l*PER + PER-1 (zero beyond the end).
+template <int PER>
+__device__ inline Found wave_find_first_reg(const float (&m)[PER], float target) {
+  const int lane = threadIdx.x & 63;
+  float local = 0.f;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) local += m[j];
+  const float inc = wave_scan_add(local);
+  float exc = __shfl_up(inc, 1, 64);
+  if (lane == 0) exc = 0.f;
+  float run = exc, before = 0.f, before_pos = 0.f;
+  int cand = -1, last_pos = -1;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    const float nxt = run + m[j];
+    if (m[j] > 0.f) { last_pos = j; before_pos = run; }
+    if (cand < 0 && nxt >= target) { cand = j; before = run; }
+    run = nxt;
   }
-  sm = wave_sum(sm);
-  const float lse = mx + logf(sm);
-  if (lane == 0) {
-    a.lse[r] = lse;
-    if (a.diag_lse) a.diag_lse[r] = lse;
+  // segments ascend with the lane id: the lowest lane that reached the target holds the answer
+  unsigned long long hit = __ballot(cand >= 0);
+  int owner;
+  if (hit) {
+    owner = __ffsll((long long)hit) - 1;
+  } else {  // target not reached: fall back to the last positive mass
+    hit = __ballot(last_pos >= 0);
+    owner = hit ? 63 - __clzll((long long)hit) : 0;
+    cand = last_pos < 0 ? 0 : last_pos;
+    before = before_pos;
   }
-  if (!is_draft) return;
+  Found f;
+  f.idx = owner * PER + __shfl(cand, owner, 64);
+  f.before = __shfl(before, owner, 64);
+  f.total = __shfl(inc, 63, 64);
+  return f;
+}
 
-  // window slot m = (m+1)-th unresolved position of the block, ascending
+// window slot m = (m+1)-th unresolved position of block b in ascending order; also counts the
+// unresolved positions.  Whole wavefront.
+__device__ inline int window_slot(const VerifyArgs& a, int b, int m, int& unresolved) {
+  const int lane = threadIdx.x & 63;
   int cnt = 0, pos = -1;
   for (int base = 0; base < a.block; base += kWave) {
     const int i = base + lane;
@@ -250,8 +231,65 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
     if (bit && rank == m) pos = i;
     cnt += __popcll(bal);
   }
-  pos = wave_max_int(pos);
-  const int window = min(a.K, cnt);
+  unresolved = cnt;
+  return wave_max_int(pos);
+}
+
+constexpr int kTilePer = 8;  // tokens per lane inside one partial tile: tiles of up to 512 tokens
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 1: per-row log-sum-exp, window slot, draft sample.  One wavefront per row.
+// PER > 0: the row's partials (at most 64*PER) and the tokens of the selected tile live in
+// registers, so every global value is loaded once and every exponential evaluated once.
+// PER == 0: any number of partials, re-read from memory.
+// ---------------------------------------------------------------------------------------------
+template <int PER>
+__global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int BK = a.B * a.K;
+  const int r = blockIdx.x * NW + wave;
+  if (r >= 2 * BK) return;
+  const bool is_draft = r < BK;
+  const int s = is_draft ? r : r - BK;
+  const int b = s / a.K, m = s % a.K;
+  const float2* P = a.partials + (size_t)r * a.nT;
+
+  // log-sum-exp of the row from the head kernel's per-tile partials
+  float mass[PER > 0 ? PER : 1];  // exp-sums of this lane's tiles relative to the row maximum
+  float mx = -INFINITY, sm = 0.f;
+  if constexpr (PER > 0) {
+    float2 p[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int t = lane * PER + j;
+      p[j] = t < a.nT ? P[t] : make_float2(-INFINITY, 0.f);
+      mx = fmaxf(mx, p[j].x);
+    }
+    mx = wave_max(mx);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      mass[j] = p[j].y > 0.f ? p[j].y * expf(p[j].x - mx) : 0.f;
+      sm += mass[j];
+    }
+  } else {
+    for (int t = lane; t < a.nT; t += kWave) mx = fmaxf(mx, P[t].x);
+    mx = wave_max(mx);
+    for (int t = lane; t < a.nT; t += kWave) {
+      const float2 p = P[t];
+      sm += p.y * expf(p.x - mx);
+    }
+  }
+  sm = wave_sum(sm);
+  const float lse = mx + logf(sm);
+  if (lane == 0) {
+    a.lse[r] = lse;
+    if (a.diag_lse) a.diag_lse[r] = lse;
+  }
+  if (!is_draft) return;
+
+  int unresolved;
+  const int pos = window_slot(a, b, m, unresolved);
+  const int window = min(a.K, unresolved);
   if (lane == 0) {
     a.slot_pos[s] = pos;
     if (m == 0) a.window[b] = window;
@@ -264,13 +302,31 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
       // x~ = min{v : sum_{w<=v} rho_w >= u}: first over vocabulary tiles, then inside the tile
       const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)pos, a.step,
                                      a.seq_base + (uint32_t)b, kStreamDraft);
-      const Found tile = wave_find_first(
-          a.nT, [&](int t) { const float2 p = P[t]; return p.y * expf(p.x - lse); }, u);
+      Found tile;
+      if constexpr (PER > 0) {
+        const float inv = 1.f / sm;  // tile probability = exp-sum / row exp-sum
+#pragma unroll
+        for (int j = 0; j < PER; ++j) mass[j] *= inv;
+        tile = wave_find_first_reg(mass, u);
+      } else {
+        tile = wave_find_first(
+            a.nT, [&](int t) { const float2 p = P[t]; return p.y * expf(p.x - lse); }, u);
+      }
       const float* L = a.logits + (size_t)r * a.ldl;
       const int v0 = tile_start(a, tile.idx);
       const int nv = min(tile_start(a, tile.idx + 1), a.V) - v0;
-      const Found in = wave_find_first(
-          nv, [&](int i) { return expf(L[v0 + i] - lse); }, u - tile.before);
+      Found in;
+      if (nv <= kWave * kTilePer) {
+        float q[kTilePer];
+#pragma unroll
+        for (int j = 0; j < kTilePer; ++j) {
+          const int i = lane * kTilePer + j;
+          q[j] = i < nv ? expf(L[v0 + i] - lse) : 0.f;
+        }
+        in = wave_find_first_reg(q, u - tile.before);
+      } else {
+        in = wave_find_first(nv, [&](int i) { return expf(L[v0 + i] - lse); }, u - tile.before);
+      }
       x = v0 + in.idx;
     }
   }
@@ -514,7 +570,10 @@ __global__ void copy_logits_kernel(const float* __restrict__ src, long ldl, floa
 
 hipError_t launch_verify(const VerifyArgs& a) {
   const int M = 2 * a.B * a.K;
-  hipLaunchKernelGGL(row_lse_draft_kernel, dim3((M + NW - 1) / NW), dim3(NT), 0, a.stream, a);
+  const dim3 g1((M + NW - 1) / NW);
+  if (a.nT <= 64 * 4) hipLaunchKernelGGL(row_lse_draft_kernel<4>, g1, dim3(NT), 0, a.stream, a);
+  else if (a.nT <= 64 * 40) hipLaunchKernelGGL(row_lse_draft_kernel<40>, g1, dim3(NT), 0, a.stream, a);
+  else hipLaunchKernelGGL(row_lse_draft_kernel<0>, g1, dim3(NT), 0, a.stream, a);
   const int gx = (a.nRC + NW - 1) / NW;
   const int nslots = a.all_slots ? a.B * a.K : a.B;
   hipLaunchKernelGGL(accept_resid_kernel, dim3(nslots, gx), dim3(NT), 0, a.stream, a);

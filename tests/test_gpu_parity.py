@@ -106,6 +106,12 @@ def test_tiled256_kernel_small_shapes(B, K, d, V):
     assert st["near_flipped"] <= B // 20
 
 
+def test_very_large_vocabulary_generic_partial_merge():
+    # more than 2560 partial tiles per row: the LSE/draft kernel re-reads partials from memory
+    ref, out, st = run_case(1, 2, 16, 64, 170001, seed=14, rho=0.8, variant=fb.FEF_GEMM_TILED, with_logits=False)
+    assert st["near_flipped"] == 0 and st["equal"] == 1
+
+
 def test_skinny_and_tiled_agree():
     W = synth.make_head(3000, 512, 5)
     hidden = synth.make_hidden(1, 8, 512, 5, 0.7, 3.0 / (0.02 * np.sqrt(512)))
