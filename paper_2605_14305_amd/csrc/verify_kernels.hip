@@ -182,13 +182,15 @@ __device__ inline Found wave_find_first(int n, F mass, float target) {
 
 // Register-resident variant of wave_find_first: lane l holds the masses of elements
 // l*PER .. l*PER + PER-1 (zero beyond the end).
-template <int PER>
+// REL: the target is a fraction of the total mass.
+template <int PER, bool REL = false>
 __device__ inline Found wave_find_first_reg(const float (&m)[PER], float target) {
   const int lane = threadIdx.x & 63;
   float local = 0.f;
 #pragma unroll
   for (int j = 0; j < PER; ++j) local += m[j];
   const float inc = wave_scan_add(local);
+  if (REL) target *= __shfl(inc, 63, 64);
   float exc = __shfl_up(inc, 1, 64);
   if (lane == 0) exc = 0.f;
   float run = exc, before = 0.f, before_pos = 0.f;
@@ -235,6 +237,7 @@ __device__ inline int window_slot(const VerifyArgs& a, int b, int m, int& unreso
   return wave_max_int(pos);
 }
 
+constexpr int kChunkPer = 16;  // residual chunks per lane in the one-wavefront final phase
 constexpr int kTilePer = 8;  // tokens per lane inside one partial tile: tiles of up to 512 tokens
 
 // ---------------------------------------------------------------------------------------------
@@ -377,6 +380,51 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
     const float* rm = a.rmass + (size_t)(a.all_slots ? s : b) * a.nRC;
     const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
                                    a.seq_base + (uint32_t)b, kStreamResidual);
+    if (a.nRC <= kWave * kChunkPer) {
+      // one wavefront, everything in registers
+      if (tid < kWave) {
+        float rmv[kChunkPer];
+#pragma unroll
+        for (int j = 0; j < kChunkPer; ++j) {
+          const int c = tid * kChunkPer + j;
+          rmv[j] = c < a.nRC ? rm[c] : 0.f;
+        }
+        const Found chunk = wave_find_first_reg<kChunkPer, true>(rmv, u);
+        int zz;
+        if (chunk.total > 0.f) {
+          const int v0 = chunk.idx * kResidChunk + tid * 4;
+          float qv[4] = {0.f, 0.f, 0.f, 0.f}, pv[4] = {0.f, 0.f, 0.f, 0.f};
+          if (v0 + 3 < a.V) {
+            const float4 q4 = *reinterpret_cast<const float4*>(Lq + v0);
+            const float4 p4 = *reinterpret_cast<const float4*>(Lp + v0);
+            qv[0] = q4.x; qv[1] = q4.y; qv[2] = q4.z; qv[3] = q4.w;
+            pv[0] = p4.x; pv[1] = p4.y; pv[2] = p4.z; pv[3] = p4.w;
+          } else {
+            for (int j = 0; j < 4; ++j)
+              if (v0 + j < a.V) { qv[j] = Lq[v0 + j]; pv[j] = Lp[v0 + j]; }
+          }
+          float rv[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            rv[j] = v0 + j < a.V ? fmaxf(expf(pv[j] - lse_p) - expf(qv[j] - lse_q), 0.f) : 0.f;
+          const Found in = wave_find_first_reg<4>(rv, u * chunk.total - chunk.before);
+          zz = chunk.idx * kResidChunk + in.idx;
+        } else {
+          // residual mass vanished in rounding although a rejection occurred: commit argmax pi
+          float best = -INFINITY;
+          int bi = INT_MAX;
+          for (int v = tid; v < a.V; v += kWave) {
+            const float l = Lp[v];
+            if (l > best) { best = l; bi = v; }
+          }
+          const float gbest = wave_max(best);
+          zz = wave_min_int(best == gbest ? bi : INT_MAX);
+        }
+        if (tid == 0) tmp.bcast_i = zz;
+      }
+      __syncthreads();
+      z = tmp.bcast_i;
+    } else {
     float Z = 0.f;
     {
       const int per = (a.nRC + NT - 1) / NT;
@@ -407,6 +455,7 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
       }
       const float gbest = block_max(best, tmp);
       z = block_min_int(best == gbest ? bi : INT_MAX, tmp);
+    }
     }
     z_conf = expf(Lp[z] - lse_p);
   }

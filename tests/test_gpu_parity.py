@@ -107,9 +107,9 @@ def test_tiled256_kernel_small_shapes(B, K, d, V):
 
 
 def test_very_large_vocabulary_generic_partial_merge():
-    # more than 2560 partial tiles per row: the LSE/draft kernel re-reads partials from memory
-    ref, out, st = run_case(1, 2, 16, 64, 170001, seed=14, rho=0.8, variant=fb.FEF_GEMM_TILED, with_logits=False)
-    assert st["near_flipped"] == 0 and st["equal"] == 1
+    # more than 2560 partial tiles and 1024 residual chunks per row: the memory-resident code paths
+    ref, out, st = run_case(2, 2, 16, 64, 270001, seed=14, rho=0.8, variant=fb.FEF_GEMM_TILED, with_logits=False)
+    assert st["near_flipped"] == 0 and st["equal"] == 2
 
 
 def test_skinny_and_tiled_agree():
