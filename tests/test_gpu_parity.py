@@ -309,3 +309,67 @@ def test_dream_shape_subset():
     torch.cuda.synchronize()
     ref1 = O.verify_step(synth.to_f64(hd1), synth.to_f64(ht1), W64, 8, wl.block, 1, step=2)
     parity.compare(ref1, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs1.diag.items()})
+
+
+def test_dream_shape_full_batch_sampled():
+    """Dream-7B-shaped batch at full size (B=32, K=16, d=3584, V=151936: 1024 rows through the
+    256x256 MFMA kernel), launched as the benchmark launches it (no diagnostics); the oracle
+    checks sampled sequences one by one."""
+    wl = synth.WORKLOADS["dream_b32"]
+    W = synth.make_head(wl.V, wl.d, 2, "bf16")
+    Wd, W64 = W.to(DEV), synth.to_f64(W)
+    vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, device=DEV)
+    assert fb.fef_select_gemm(vs._params(), wl.K) == fb.FEF_GEMM_TILED256
+    hd, ht = synth.make_round(wl, 2, 1, 7)
+    tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 2, step=7, pos_base=64)
+    torch.cuda.synchronize()
+    equal = 0
+    for b in (0, 13, 31):
+        r = O.verify_step(synth.to_f64(hd[b:b + 1]), synth.to_f64(ht[b:b + 1]), W64, wl.K, wl.block, 2, step=7,
+                          seq_base=b, pos_base=64)
+        st = parity.compare(r, _np(tok)[b:b + 1], _np(acc)[b:b + 1], _np(rem)[b:b + 1])
+        equal += st["equal"]
+        print(f"seq {b}: accept_len {r.accept_len[0]} {st}", flush=True)
+    assert equal >= 2
+    # whole-batch properties that hold at any size
+    t, a_ = _np(tok), _np(acc)
+    assert np.all((a_ >= 0) & (a_ <= wl.K))
+    for b in range(wl.B):
+        c = min(a_[b] + 1, wl.K)
+        assert np.all((t[b, :c] >= 0) & (t[b, :c] < wl.V)) and np.all(t[b, c:] == -1)
+        assert _np(rem)[b].sum() == wl.block - c
+
+
+def test_acceptance_sweep_matches_theorem_2(llada_head):
+    """Acceptance-rate sweep at scale (B=64, K=16, d=4096, V=126464): for each (rho, tau) the mean
+    committed length of the HIP path matches Theorem 2 evaluated on the per-slot acceptance
+    probabilities alpha = sum min(p, q) that the same call reports, and sampled sequences match the
+    oracle.  Prints mean alpha, mean C, E[C_k] and the idealised acceleration E[C_k]/2."""
+    wl, W, Wd, W64 = llada_head
+    B, K, block = 64, 16, 32
+    vs = fb.VerifyStep(B, K, block, wl.d, wl.V, device=DEV, diag=True)
+    alphas_seen = []
+    for rho in (0.5, 0.9, 0.99):
+        for tau in (0.5, 1.0):
+            C, EC, al = [], [], []
+            for step in range(3):
+                hd, ht = synth.make_hidden(B, K, wl.d, 5, rho, wl.sigma_h, "bf16", 0, step)
+                tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 5, step=step, temperature=tau)
+                torch.cuda.synchronize()
+                a_, alpha = _np(acc), _np(vs.diag["alpha"]).astype(np.float64)
+                C.append(np.minimum(a_ + 1, K))
+                EC.append([O.expected_committed(alpha[b]) for b in range(B)])
+                al.append(alpha.mean())
+                if step == 0:
+                    for b in (3, 60):
+                        r = O.verify_step(synth.to_f64(hd[b:b + 1]), synth.to_f64(ht[b:b + 1]), W64, K, block, 5,
+                                          step=step, seq_base=b, temperature=tau)
+                        diag = {"alpha": alpha[b:b + 1], "resid_mass": _np(vs.diag["resid_mass"])[b:b + 1]}
+                        parity.compare(r, _np(tok)[b:b + 1], a_[b:b + 1], _np(rem)[b:b + 1], diag)
+            C, EC = np.concatenate(C).astype(np.float64), np.concatenate(EC)
+            se = C.std() / np.sqrt(C.size) + 1e-9
+            print(f"rho={rho} tau={tau}: mean alpha {np.mean(al):.3f}  mean C {C.mean():.3f}  "
+                  f"Theorem-2 E[C] {EC.mean():.3f}  S=E[C]/2 {EC.mean() / 2:.3f}  (n={C.size})", flush=True)
+            assert abs(C.mean() - EC.mean()) < 4 * se + 0.02
+            alphas_seen.append(np.mean(al))
+    assert min(alphas_seen) < 0.35 and max(alphas_seen) > 0.8     # the sweep spans low and high acceptance
