@@ -50,7 +50,7 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 1
+#define FEF_ABI_VERSION 2
 
 typedef enum {
   FEF_OK = 0,
@@ -106,6 +106,18 @@ typedef struct {
   void* stream;                /* hipStream_t; NULL = the null stream                        */
   void* ev_head_begin;         /* optional hipEvent_t pair (both or neither) that receives    */
   void* ev_head_end;           /* the vocabulary-head kernel's own start / stop timestamps    */
+  /* Optional device-side state of Algorithm 2's outer loops, so that a caller can enqueue the
+   * rounds of a block back to back without reading anything back (all NULL = not used):       */
+  int32_t n_pass;              /* N_step, the number of generation passes; >= 1 with seq_pass */
+  int32_t* seq_pass;           /* [B] in/out: pass s of each sequence.  When given it replaces
+                                  final_pass (a sequence is on its final pass iff s >= n_pass-1);
+                                  s is incremented when LowConf fires and set to n_pass when the
+                                  final pass resolves the block (the sequence is then done and
+                                  further rounds leave it untouched)                           */
+  int32_t* seq_rounds;         /* [B] in/out: incremented when the sequence had a non-empty
+                                  window in this round                                        */
+  int32_t* tokens_state;       /* [B, block] in/out: X restricted to the block; committed tokens
+                                  are written at their positions, re-masked positions get -1   */
 } fef_params;
 
 /* Bytes of device workspace a call with these sizes needs (depends on B, d, V, dtype,

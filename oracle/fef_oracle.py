@@ -273,8 +273,9 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
 
     # S6: low-confidence re-corruption once the block is resolved
     lowconf_gap = np.full(B, np.inf)
-    if not final_pass:
-        for b in range(B):
+    final = np.broadcast_to(np.asarray(final_pass, dtype=bool), (B,))   # scalar or one flag per sequence
+    for b in range(B):
+        if not final[b]:
             if new_mask[b].any():
                 continue
             cand = pmask[b] if lowconf_scope == 0 else np.ones(block, np.uint8)

@@ -40,6 +40,8 @@ class fef_params(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
         ("ev_head_begin", ctypes.c_void_p), ("ev_head_end", ctypes.c_void_p),
+        ("n_pass", ctypes.c_int32), ("seq_pass", ctypes.c_void_p), ("seq_rounds", ctypes.c_void_p),
+        ("tokens_state", ctypes.c_void_p),
     ]
 
 
@@ -183,7 +185,8 @@ class VerifyStep:
 
     def __call__(self, h_draft, h_target, W_vocab, seed, *, temperature=1.0, step=0, seq_base=0,
                  pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0, mask_in=None, pass_mask=None,
-                 conf=None, draft_tokens=None, head_events=None):
+                 conf=None, draft_tokens=None, head_events=None, n_pass=0, seq_pass=None, seq_rounds=None,
+                 tokens_state=None):
         for t, shape in ((h_draft, (self.B, self.K, self.d)), (h_target, (self.B, self.K, self.d)),
                          (W_vocab, (self.V, self.d))):
             assert tuple(t.shape) == shape and t.dtype == self.torch_dtype and t.is_contiguous()
@@ -191,7 +194,9 @@ class VerifyStep:
         for t, dt, shape in ((mask_in, torch.uint8, (self.B, self.block)),
                              (pass_mask, torch.uint8, (self.B, self.block)),
                              (conf, torch.float32, (self.B, self.block)),
-                             (draft_tokens, torch.int32, (self.B, self.K))):
+                             (draft_tokens, torch.int32, (self.B, self.K)),
+                             (seq_pass, torch.int32, (self.B,)), (seq_rounds, torch.int32, (self.B,)),
+                             (tokens_state, torch.int32, (self.B, self.block))):
             if t is not None:
                 assert t.dtype == dt and tuple(t.shape) == shape and t.is_contiguous() and t.device.type == "cuda"
         p = self._params(temperature=temperature, step=step, seq_base=seq_base, pos_base=pos_base,
@@ -200,6 +205,10 @@ class VerifyStep:
         p.pass_mask = None if pass_mask is None else pass_mask.data_ptr()
         p.conf = None if conf is None else conf.data_ptr()
         p.draft_tokens = None if draft_tokens is None else draft_tokens.data_ptr()
+        p.n_pass = n_pass
+        p.seq_pass = None if seq_pass is None else seq_pass.data_ptr()
+        p.seq_rounds = None if seq_rounds is None else seq_rounds.data_ptr()
+        p.tokens_state = None if tokens_state is None else tokens_state.data_ptr()
         p.workspace = self.workspace.data_ptr()
         p.workspace_bytes = self.workspace.numel()
         p.stream = torch.cuda.current_stream(self.device).cuda_stream
@@ -208,3 +217,31 @@ class VerifyStep:
         fef_verify_step(p, h_draft, h_target, W_vocab, self.K, self.block, seed, self.out_tokens,
                         self.out_accept_len, self.out_remask)
         return self.out_tokens, self.out_accept_len, self.out_remask
+
+
+class BlockDecoder:
+    """Device-side state of Algorithm 2's outer loops for one block of B sequences: block mask,
+    pass set, confidences, tokens, per-sequence pass and round counters.  `round()` enqueues one
+    speculative round on top of that state and reads nothing back, so the rounds of a block can
+    be queued back to back; a sequence that has finished its last pass is left untouched."""
+
+    def __init__(self, step, n_pass, n_rm=-1, lowconf_scope=0):
+        self.vs, self.n_pass, self.n_rm, self.lowconf_scope = step, n_pass, n_rm, lowconf_scope
+        B, block, dev = step.B, step.block, step.device
+        self.mask = torch.ones(B, block, dtype=torch.uint8, device=dev)
+        self.pass_mask = torch.zeros(B, block, dtype=torch.uint8, device=dev)
+        self.conf = torch.zeros(B, block, dtype=torch.float32, device=dev)
+        self.tokens = torch.full((B, block), -1, dtype=torch.int32, device=dev)
+        self.seq_pass = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.seq_rounds = torch.zeros(B, dtype=torch.int32, device=dev)
+
+    def max_rounds(self):
+        n_rm = self.vs.block // 2 if self.n_rm < 0 else min(self.n_rm, self.vs.block)
+        return self.vs.block + (self.n_pass - 1) * max(n_rm, 1)
+
+    def round(self, h_draft, h_target, W_vocab, seed, step, **kw):
+        self.vs(h_draft, h_target, W_vocab, seed, step=step, n_rm=self.n_rm, lowconf_scope=self.lowconf_scope,
+                mask_in=self.mask, pass_mask=self.pass_mask, conf=self.conf, n_pass=self.n_pass,
+                seq_pass=self.seq_pass, seq_rounds=self.seq_rounds, tokens_state=self.tokens, **kw)
+        # out_remask of this round is the mask of the next one (device-to-device, stream ordered)
+        self.mask.copy_(self.vs.out_remask)

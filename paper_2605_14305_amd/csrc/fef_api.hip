@@ -49,6 +49,8 @@ fef_status check_sizes(const fef_params* p, int32_t K, int32_t block) {
     return fail(FEF_ERR_INVALID_ARG, "B*K = %ld exceeds 2^24 rows per call", (long)p->B * K);
   if (p->lowconf_scope != 0 && p->lowconf_scope != 1)
     return fail(FEF_ERR_INVALID_ARG, "lowconf_scope must be 0 or 1");
+  if (p->seq_pass && p->n_pass < 1)
+    return fail(FEF_ERR_INVALID_ARG, "seq_pass needs n_pass >= 1 (got %d)", p->n_pass);
   if (!p->conf && (p->pass_mask || p->lowconf_scope == 1))
     return fail(FEF_ERR_INVALID_ARG, "conf may be NULL only with pass_mask NULL and lowconf_scope 0");
   return FEF_OK;
@@ -198,6 +200,8 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   v.n_rm = prm->n_rm; v.final_pass = prm->final_pass; v.lowconf_scope = prm->lowconf_scope;
   v.mask_in = prm->mask_in; v.pass_mask = prm->pass_mask; v.conf = prm->conf;
   v.draft_tokens_in = prm->draft_tokens;
+  v.n_pass = prm->n_pass; v.seq_pass = prm->seq_pass; v.seq_rounds = prm->seq_rounds;
+  v.tokens_state = prm->tokens_state;
   v.lse = (float*)(ws + L.off_lse);
   v.xdraft = (int32_t*)(ws + L.off_xdraft);
   v.slot_pos = (int32_t*)(ws + L.off_slot_pos);

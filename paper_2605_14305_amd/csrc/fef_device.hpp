@@ -96,6 +96,10 @@ struct VerifyArgs {
   uint8_t* pass_mask;
   float* conf;
   const int32_t* draft_tokens_in;
+  int n_pass;                // with seq_pass: number of generation passes
+  int32_t* seq_pass;         // [B] optional per-sequence pass counter (replaces final_pass)
+  int32_t* seq_rounds;       // [B] optional round counter
+  int32_t* tokens_state;     // [B, block] optional token state of the block
   // workspace
   float* lse;               // [2*B*K]
   int32_t* xdraft;          // [B*K]

@@ -492,7 +492,8 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
   for (int i = tid; i < a.block; i += NT) unresolved |= s_mask[i];
   unresolved = block_max_int(unresolved, tmp);
 
-  const bool fire = !unresolved && !a.final_pass;
+  const bool final = a.seq_pass ? a.seq_pass[b] >= a.n_pass - 1 : a.final_pass != 0;
+  const bool fire = !unresolved && !final;
   if (fire) {
     // LowConf: rank every candidate by (confidence, position); the n_rm lowest are re-masked
     const int n_rm = a.n_rm < 0 ? a.block / 2 : a.n_rm;
@@ -510,10 +511,21 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
     }
     __syncthreads();
   }
+  if (a.tokens_state && tid < committed)
+    a.tokens_state[row + a.slot_pos[b * a.K + tid]] = tid < acc_len ? st.x[tid] : z;
+  __syncthreads();  // seq_pass was read above by every thread; the token writes precede the -1s
   for (int i = tid; i < a.block; i += NT) {
     a.out_remask[row + i] = s_mask[i];
     if (a.pass_mask) a.pass_mask[row + i] = fire ? 0 : s_cand[i];
     if (a.conf) a.conf[row + i] = s_conf[i];
+    if (a.tokens_state && fire && s_mask[i]) a.tokens_state[row + i] = -1;
+  }
+  if (tid == 0) {
+    if (a.seq_pass) {
+      if (fire) a.seq_pass[b] += 1;
+      else if (!unresolved && final) a.seq_pass[b] = a.n_pass;
+    }
+    if (a.seq_rounds && window > 0) a.seq_rounds[b] += 1;
   }
 }
 
