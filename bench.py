@@ -52,10 +52,9 @@ class HipEvents:
         self.hip.hipEventDestroy(e)
 
 
-def head_bytes(wl, skinny):
-    """Algorithmic HBM bytes of one vocabulary-head launch: W once, H once, fp32 logits
-    written once, the per-tile (max, sum exp) partials."""
-    M = 2 * wl.B * wl.K
+def head_bytes(wl, skinny, M):
+    """Algorithmic HBM bytes of one vocabulary-head launch over M rows: W once, H once, fp32
+    logits written once, the per-tile (max, sum exp) partials."""
     esz = 2 if wl.dtype == "bf16" else 4
     nT = min(-(-wl.V // 16), 256) if skinny else -(-wl.V // 64)
     return wl.V * wl.d * esz + M * wl.d * esz + M * wl.V * 4 + M * nT * 8
@@ -96,6 +95,9 @@ def main():
     ap.add_argument("--copy-probe", type=int, default=0, metavar="N",
                     help="instead of the benchmark, run the library's plain copy kernel N times on a "
                          "1 GiB buffer (profiler byte-counter calibration)")
+    ap.add_argument("--split", action="store_true",
+                    help="the method's own call order: a draft-only call, then a target-only call "
+                         "(W is read twice); the roofline entry then describes the target call's head launch")
     ap.add_argument("--events", choices=["inline", "separate"], default="inline",
                     help="record the head-kernel events inside the timed steps, or in a second pass")
     args = ap.parse_args()
@@ -126,13 +128,20 @@ def main():
     rounds_d = [(hd.to(dev), ht.to(dev)) for hd, ht in rounds]
 
     vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, dtype=wl.dtype, device=dev)
-    variant = fb.fef_select_gemm(vs._params(), wl.K)
+    p0 = vs._params()
+    p0.phase = fb.FEF_PHASE_DRAFT if args.split else fb.FEF_PHASE_FUSED
+    variant = fb.fef_select_gemm(p0, wl.K)
     ev = HipEvents()
     pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
 
     def step(i, events=None):
         hd, ht = rounds_d[i % n_rounds]
-        vs(hd, ht, Wd, args.seed, step=i, temperature=wl.temperature, head_events=events)
+        if args.split:
+            vs(hd, None, Wd, args.seed, step=i, temperature=wl.temperature, phase=fb.FEF_PHASE_DRAFT)
+            vs(None, ht, Wd, args.seed, step=i, temperature=wl.temperature, phase=fb.FEF_PHASE_TARGET,
+               head_events=events)
+        else:
+            vs(hd, ht, Wd, args.seed, step=i, temperature=wl.temperature, head_events=events)
 
     for i in range(args.warmup):
         step(i)
@@ -152,8 +161,8 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
     positions = wl.B * wl.K
-    M = 2 * positions
-    hb = head_bytes(wl, variant == fb.FEF_GEMM_SKINNY)
+    M = positions if args.split else 2 * positions   # rows through one head launch
+    hb = head_bytes(wl, variant == fb.FEF_GEMM_SKINNY, M)
     flops = 2.0 * M * wl.V * wl.d
     hbm_time, mfma_time = hb / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if hbm_time >= mfma_time:
@@ -186,7 +195,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "K": wl.K, "block": wl.block, "d": wl.d, "V": wl.V,
                    "rho": wl.rho, "logit_std": wl.logit_std, "temperature": wl.temperature,
-                   "rows_through_head": M},
+                   "rows_through_head": M, "call_order": "draft+target" if args.split else "fused"},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -65,7 +65,8 @@ typedef enum {
   FEF_F32 = 1   /* all three are float32; plain FMA path for tiny instances                */
 } fef_dtype;
 
-/* Which vocabulary-head kernel to run.  AUTO picks by (dtype, M = 2*B*K, d). */
+/* Which vocabulary-head kernel to run.  AUTO picks by (dtype, M, d), M = rows through the head
+ * in this call: 2*B*K fused, B*K in a DRAFT or TARGET call. */
 typedef enum {
   FEF_GEMM_AUTO = 0,
   FEF_GEMM_SKINNY = 1, /* bf16, M <= 16, d in {512, 3584, 4096}: W streamed once, split-k  */
@@ -73,6 +74,17 @@ typedef enum {
   FEF_GEMM_F32 = 3,    /* f32, any shape: reference-grade FMA kernel                       */
   FEF_GEMM_TILED256 = 4 /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)        */
 } fef_gemm_variant;
+
+/* In Algorithm 2 the verification inputs X^(j_m) carry the draft prefix, so a real target
+ * forward can only run after the draft tokens exist.  FUSED does both laws in one pass over W
+ * (hidden states given up front).  DRAFT projects the draft rows only, samples x~ and writes
+ * them to out_tokens (out_accept_len / out_remask are not touched and may be NULL; h_target is
+ * not read and may be NULL).  TARGET projects the target rows only and finishes the round; it
+ * must follow a DRAFT call with the same sizes, mask_in, seed, step and the SAME workspace,
+ * left untouched in between (it holds the draft logits, their log-sum-exp and x~); h_draft is
+ * not read and may be NULL.  DRAFT + TARGET give bit-identical results to FUSED when both
+ * use the same head kernel, and read W twice. */
+typedef enum { FEF_PHASE_FUSED = 0, FEF_PHASE_DRAFT = 1, FEF_PHASE_TARGET = 2 } fef_phase;
 
 typedef struct {
   uint32_t struct_size;   /* = sizeof(fef_params); rejects callers built against another ABI */
@@ -118,6 +130,8 @@ typedef struct {
                                   window in this round                                        */
   int32_t* tokens_state;       /* [B, block] in/out: X restricted to the block; committed tokens
                                   are written at their positions, re-masked positions get -1   */
+  int32_t phase;               /* fef_phase: the call order of the method when the target
+                                  forward needs the draft tokens (see fef_phase)              */
 } fef_params;
 
 /* Bytes of device workspace a call with these sizes needs (depends on B, d, V, dtype,

@@ -18,6 +18,7 @@ FEF_ERR_HIP = -4
 FEF_BF16, FEF_F32 = 0, 1
 FEF_GEMM_AUTO, FEF_GEMM_SKINNY, FEF_GEMM_TILED, FEF_GEMM_F32, FEF_GEMM_TILED256 = 0, 1, 2, 3, 4
 FEF_MAX_K, FEF_MAX_BLOCK = 64, 4096
+FEF_PHASE_FUSED, FEF_PHASE_DRAFT, FEF_PHASE_TARGET = 0, 1, 2
 
 EXPORTS = ["fef_workspace_bytes", "fef_verify_step", "fef_select_gemm", "fef_uniform",
            "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe"]
@@ -41,7 +42,7 @@ class fef_params(ctypes.Structure):
         ("stream", ctypes.c_void_p),
         ("ev_head_begin", ctypes.c_void_p), ("ev_head_end", ctypes.c_void_p),
         ("n_pass", ctypes.c_int32), ("seq_pass", ctypes.c_void_p), ("seq_rounds", ctypes.c_void_p),
-        ("tokens_state", ctypes.c_void_p),
+        ("tokens_state", ctypes.c_void_p), ("phase", ctypes.c_int32),
     ]
 
 
@@ -168,6 +169,8 @@ class VerifyStep:
         nbytes = fef_workspace_bytes(p, K, block)
         if nbytes == 0:
             raise FefError(FEF_ERR_INVALID_ARG, fef_last_error())
+        p.phase = FEF_PHASE_DRAFT          # split calls may pick another head kernel and layout
+        nbytes = max(nbytes, fef_workspace_bytes(p, K, block))
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
     def _params(self, **kw):
@@ -186,9 +189,11 @@ class VerifyStep:
     def __call__(self, h_draft, h_target, W_vocab, seed, *, temperature=1.0, step=0, seq_base=0,
                  pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0, mask_in=None, pass_mask=None,
                  conf=None, draft_tokens=None, head_events=None, n_pass=0, seq_pass=None, seq_rounds=None,
-                 tokens_state=None):
+                 tokens_state=None, phase=FEF_PHASE_FUSED):
         for t, shape in ((h_draft, (self.B, self.K, self.d)), (h_target, (self.B, self.K, self.d)),
                          (W_vocab, (self.V, self.d))):
+            if t is None:
+                continue
             assert tuple(t.shape) == shape and t.dtype == self.torch_dtype and t.is_contiguous()
             assert t.device.type == "cuda"
         for t, dt, shape in ((mask_in, torch.uint8, (self.B, self.block)),
@@ -205,6 +210,7 @@ class VerifyStep:
         p.pass_mask = None if pass_mask is None else pass_mask.data_ptr()
         p.conf = None if conf is None else conf.data_ptr()
         p.draft_tokens = None if draft_tokens is None else draft_tokens.data_ptr()
+        p.phase = phase
         p.n_pass = n_pass
         p.seq_pass = None if seq_pass is None else seq_pass.data_ptr()
         p.seq_rounds = None if seq_rounds is None else seq_rounds.data_ptr()

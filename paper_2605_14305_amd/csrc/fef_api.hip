@@ -49,6 +49,8 @@ fef_status check_sizes(const fef_params* p, int32_t K, int32_t block) {
     return fail(FEF_ERR_INVALID_ARG, "B*K = %ld exceeds 2^24 rows per call", (long)p->B * K);
   if (p->lowconf_scope != 0 && p->lowconf_scope != 1)
     return fail(FEF_ERR_INVALID_ARG, "lowconf_scope must be 0 or 1");
+  if (p->phase != FEF_PHASE_FUSED && p->phase != FEF_PHASE_DRAFT && p->phase != FEF_PHASE_TARGET)
+    return fail(FEF_ERR_INVALID_ARG, "unknown phase %d", p->phase);
   if (p->seq_pass && p->n_pass < 1)
     return fail(FEF_ERR_INVALID_ARG, "seq_pass needs n_pass >= 1 (got %d)", p->n_pass);
   if (!p->conf && (p->pass_mask || p->lowconf_scope == 1))
@@ -57,7 +59,7 @@ fef_status check_sizes(const fef_params* p, int32_t K, int32_t block) {
 }
 
 fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
-  const long M = 2L * p->B * K;
+  const long M = (p->phase == FEF_PHASE_FUSED ? 2L : 1L) * p->B * K;  // rows through the head in this call
   int v = p->gemm_variant;
   if (v == FEF_GEMM_AUTO) {
     if (p->dtype == FEF_F32) v = FEF_GEMM_F32;
@@ -158,9 +160,10 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   Layout L;
   fef_status s = make_layout(prm, K, block, &L);
   if (s != FEF_OK) return s;
-  if (!h_draft || !h_target || !W_vocab)
+  const int phase = prm->phase;
+  if ((!h_draft && phase != FEF_PHASE_TARGET) || (!h_target && phase != FEF_PHASE_DRAFT) || !W_vocab)
     return fail(FEF_ERR_INVALID_ARG, "h_draft, h_target and W_vocab must not be NULL");
-  if (!out_tokens || !out_accept_len || !out_remask)
+  if (!out_tokens || ((!out_accept_len || !out_remask) && phase != FEF_PHASE_DRAFT))
     return fail(FEF_ERR_INVALID_ARG, "out_tokens, out_accept_len and out_remask must not be NULL");
   if (((uintptr_t)h_draft | (uintptr_t)h_target | (uintptr_t)W_vocab) & 15)
     return fail(FEF_ERR_INVALID_ARG, "h_draft, h_target and W_vocab must be 16-byte aligned");
@@ -177,9 +180,11 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   fef::HeadArgs h;
   h.h_draft = h_draft; h.h_target = h_target; h.W = W_vocab;
   h.BK = prm->B * K; h.d = prm->d; h.V = prm->V;
+  h.row0 = phase == FEF_PHASE_TARGET ? h.BK : 0;
+  h.nrows = phase == FEF_PHASE_FUSED ? 2 * h.BK : h.BK;
   h.inv_tau = 1.0f / prm->temperature;
-  h.logits = (float*)(ws + L.off_logits); h.ldl = L.ldl;
-  h.partials = (float2*)(ws + L.off_partials); h.nT = L.nT;
+  h.logits = (float*)(ws + L.off_logits) + (size_t)h.row0 * L.ldl; h.ldl = L.ldl;
+  h.partials = (float2*)(ws + L.off_partials) + (size_t)h.row0 * L.nT; h.nT = L.nT;
   h.stream = stream;
   h.ev_begin = (hipEvent_t)prm->ev_head_begin; h.ev_end = (hipEvent_t)prm->ev_head_end;
   hipError_t e;
@@ -194,7 +199,8 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   fef::VerifyArgs v;
   memset(&v, 0, sizeof v);
   v.B = prm->B; v.K = K; v.block = block; v.V = prm->V;
-  v.ldl = L.ldl; v.logits = h.logits; v.partials = h.partials; v.nT = L.nT;
+  v.row0 = h.row0; v.nrows = h.nrows; v.phase = phase;
+  v.ldl = L.ldl; v.logits = (float*)(ws + L.off_logits); v.partials = (float2*)(ws + L.off_partials); v.nT = L.nT;
   v.tile_unit = L.tile_unit; v.tile_T = L.tile_T; v.tile_G = L.nT;
   v.seed = seed; v.step = prm->step; v.seq_base = prm->seq_base; v.pos_base = prm->pos_base;
   v.n_rm = prm->n_rm; v.final_pass = prm->final_pass; v.lowconf_scope = prm->lowconf_scope;

@@ -51,10 +51,11 @@ struct HeadArgs {
   const void* h_target;  // [BK, d]
   const void* W;         // [V, d]
   int BK, d, V;
+  int row0, nrows;       // rows [row0, row0 + nrows) of the stacked [draft; target] matrix
   float inv_tau;
-  float* logits;         // [2*BK, ldl]
+  float* logits;         // [nrows, ldl]: already points at row row0
   long ldl;
-  float2* partials;      // [2*BK, nT]
+  float2* partials;      // [nrows, nT]: already points at row row0
   int nT;                // partial tiles per row
   hipStream_t stream;
   hipEvent_t ev_begin, ev_end;  // optional: receive the kernel's own start / stop timestamps
@@ -84,6 +85,8 @@ struct SeqState {
 
 struct VerifyArgs {
   int B, K, block, V;
+  int row0, nrows;          // logits rows the LSE / draft kernel handles in this call
+  int phase;                // 0 fused, 1 draft half only, 2 target half only
   long ldl;
   const float* logits;      // [2*B*K, ldl]
   const float2* partials;   // [2*B*K, nT]

@@ -15,9 +15,11 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // also drain the vector-memory counter and with it the W tiles prefetched for later steps.
 __device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// Row r of this launch (0 <= r < nrows) is row row0 + r of the stacked [draft; target] matrix.
 __device__ inline const __bf16* h_row(const HeadArgs& a, int r) {
-  return r < a.BK ? (const __bf16*)a.h_draft + (size_t)r * a.d
-                  : (const __bf16*)a.h_target + (size_t)(r - a.BK) * a.d;
+  const int g = a.row0 + r;
+  return g < a.BK ? (const __bf16*)a.h_draft + (size_t)g * a.d
+                  : (const __bf16*)a.h_target + (size_t)(g - a.BK) * a.d;
 }
 
 // LDS tiles of bf16 are [rows][64 k] = 128 B per row.  The LDS has 64 four-byte banks, so two

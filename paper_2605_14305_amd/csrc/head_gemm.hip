@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
   __shared__ float out[16][kSkinnyOutTiles * 16 + 4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, g = lane >> 4;
-  const int M = 2 * a.BK;
+  const int M = a.nrows;
   const int kofs = wave * (KS * 32) + g * 8;  // first k of this lane; k-step s adds 32 s
 
   bf16x8 hreg[KS];
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kTiledThreads) void head_tiled_kernel(HeadArgs a, i
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int j32 = lane & 31, h = lane >> 5;
-  const int M = 2 * a.BK;
+  const int M = a.nrows;
 
   // XCD-aware order: workgroup ids round-robin over the 8 XCDs, so ids with the same id % 8
   // share an L2.  Within one XCD, consecutive workgroups walk the row tiles of one token tile.
@@ -267,8 +267,9 @@ __global__ __launch_bounds__(kWave) void head_f32_kernel(HeadArgs a) {
   const int t = blockIdx.x, r = blockIdx.y;
   const int v = t * kTiledTn + lane;
   const bool valid = v < a.V;
-  const float* hp = r < a.BK ? (const float*)a.h_draft + (size_t)r * a.d
-                             : (const float*)a.h_target + (size_t)(r - a.BK) * a.d;
+  const int g = a.row0 + r;
+  const float* hp = g < a.BK ? (const float*)a.h_draft + (size_t)g * a.d
+                             : (const float*)a.h_target + (size_t)(g - a.BK) * a.d;
   const float* wp = (const float*)a.W + (size_t)(valid ? v : a.V - 1) * a.d;
   float acc = 0.f;
   for (int k = 0; k < a.d; ++k) acc = fmaf(hp[k], wp[k], acc);
@@ -313,7 +314,7 @@ hipError_t launch_head_skinny_nb(const HeadArgs& a) {
 hipError_t launch_head_skinny(const HeadArgs& a) { return launch_head_skinny_nb<4>(a); }
 
 hipError_t launch_head_tiled(const HeadArgs& a) {
-  const int M = 2 * a.BK;
+  const int M = a.nrows;
   const int m_tiles = (M + TM - 1) / TM, n_tiles = (a.V + TN - 1) / TN;
   const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
   hipExtLaunchKernelGGL(head_tiled_kernel, dim3((unsigned)grid), dim3(kTiledThreads), 0, a.stream,
@@ -322,7 +323,7 @@ hipError_t launch_head_tiled(const HeadArgs& a) {
 }
 
 hipError_t launch_head_f32(const HeadArgs& a) {
-  hipExtLaunchKernelGGL(head_f32_kernel, dim3(a.nT, 2 * a.BK), dim3(kWave), 0, a.stream, a.ev_begin,
+  hipExtLaunchKernelGGL(head_f32_kernel, dim3(a.nT, a.nrows), dim3(kWave), 0, a.stream, a.ev_begin,
                         a.ev_end, 0, a);
   return hipGetLastError();
 }

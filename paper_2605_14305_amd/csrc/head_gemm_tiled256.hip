@@ -65,7 +65,7 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int j32 = lane & 31, h = lane >> 5;
-  const int M = 2 * a.BK;
+  const int M = a.nrows;
 
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
   const int nt = xcd + 8 * (seq / m_tiles), mt = seq % m_tiles;
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
 }  // namespace
 
 hipError_t launch_head_tiled256(const HeadArgs& a) {
-  const int M = 2 * a.BK;
+  const int M = a.nrows;
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (a.V + BN - 1) / BN;
   const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
   hipExtLaunchKernelGGL(head_tiled256_kernel<2>, dim3((unsigned)grid), dim3(512), 0, a.stream,

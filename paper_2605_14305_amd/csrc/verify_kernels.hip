@@ -250,8 +250,8 @@ template <int PER>
 __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int BK = a.B * a.K;
-  const int r = blockIdx.x * NW + wave;
-  if (r >= 2 * BK) return;
+  const int r = a.row0 + blockIdx.x * NW + wave;
+  if (r >= a.row0 + a.nrows) return;
   const bool is_draft = r < BK;
   const int s = is_draft ? r : r - BK;
   const int b = s / a.K, m = s % a.K;
@@ -336,6 +336,7 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
   if (lane == 0) {
     a.xdraft[s] = x;
     if (a.diag_draft_tokens) a.diag_draft_tokens[s] = x;
+    if (a.phase == 1) a.out_tokens[s] = x;  // draft-only call: the caller gets the draft tokens
   }
 }
 
@@ -630,21 +631,22 @@ __global__ void copy_logits_kernel(const float* __restrict__ src, long ldl, floa
 }  // namespace
 
 hipError_t launch_verify(const VerifyArgs& a) {
-  const int M = 2 * a.B * a.K;
-  const dim3 g1((M + NW - 1) / NW);
+  const dim3 g1((a.nrows + NW - 1) / NW);
   if (a.nT <= 64 * 4) hipLaunchKernelGGL(row_lse_draft_kernel<4>, g1, dim3(NT), 0, a.stream, a);
   else if (a.nT <= 64 * 40) hipLaunchKernelGGL(row_lse_draft_kernel<40>, g1, dim3(NT), 0, a.stream, a);
   else hipLaunchKernelGGL(row_lse_draft_kernel<0>, g1, dim3(NT), 0, a.stream, a);
-  const int gx = (a.nRC + NW - 1) / NW;
-  const int nslots = a.all_slots ? a.B * a.K : a.B;
-  hipLaunchKernelGGL(accept_resid_kernel, dim3(nslots, gx), dim3(NT), 0, a.stream, a);
-  hipLaunchKernelGGL(finalize_kernel, dim3(a.B), dim3(NT), 0, a.stream, a);
+  if (a.phase != 1) {  // everything after the draft sample needs the target laws
+    const int gx = (a.nRC + NW - 1) / NW;
+    const int nslots = a.all_slots ? a.B * a.K : a.B;
+    hipLaunchKernelGGL(accept_resid_kernel, dim3(nslots, gx), dim3(NT), 0, a.stream, a);
+    hipLaunchKernelGGL(finalize_kernel, dim3(a.B), dim3(NT), 0, a.stream, a);
+  }
   if (a.diag_logits) {
-    const long rows = M;
+    const long rows = a.nrows;
     const long n = rows * a.V;
     const int blocks = (int)((n + 255) / 256 > 65535 ? 65535 : (n + 255) / 256);
-    hipLaunchKernelGGL(copy_logits_kernel, dim3(blocks), dim3(256), 0, a.stream, a.logits, a.ldl,
-                       a.diag_logits, a.V, rows);
+    hipLaunchKernelGGL(copy_logits_kernel, dim3(blocks), dim3(256), 0, a.stream,
+                       a.logits + (size_t)a.row0 * a.ldl, a.ldl, a.diag_logits + (size_t)a.row0 * a.V, a.V, rows);
   }
   return hipGetLastError();
 }

@@ -101,6 +101,8 @@ def test_argument_validation_happens_on_the_host(lib):
     p = good(); cases.append((p, {"out": 0}, fb.FEF_ERR_INVALID_ARG))
     p = good(); cases.append((p, {"h": 0x1008}, fb.FEF_ERR_INVALID_ARG))                # misaligned
     p = good(); p.ev_head_begin = 0x3000; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))   # pair needed
+    p = good(); p.phase = 5; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
+    p = good(); p.phase = fb.FEF_PHASE_TARGET; cases.append((p, {"out": 0}, fb.FEF_ERR_INVALID_ARG))
     p = good(); p.seq_pass = 0x4000; p.n_pass = 0; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
     p = good(); p.workspace = 0; cases.append((p, {}, fb.FEF_ERR_WORKSPACE))
     p = good(); p.workspace = 0x10010; cases.append((p, {}, fb.FEF_ERR_WORKSPACE))

@@ -373,3 +373,43 @@ def test_acceptance_sweep_matches_theorem_2(llada_head):
             assert abs(C.mean() - EC.mean()) < 4 * se + 0.02
             alphas_seen.append(np.mean(al))
     assert min(alphas_seen) < 0.35 and max(alphas_seen) > 0.8     # the sweep spans low and high acceptance
+
+
+@pytest.mark.parametrize("B,K,d,V,variant", [(1, 8, 512, 3000, fb.FEF_GEMM_AUTO), (2, 8, 512, 3000, fb.FEF_GEMM_AUTO),
+                                              (6, 4, 128, 1000, fb.FEF_GEMM_TILED), (40, 4, 64, 700, fb.FEF_GEMM_TILED256)])
+def test_split_draft_then_target_call_order(B, K, d, V, variant):
+    """The method's own call order: draft laws and draft tokens first, target laws afterwards
+    (the verification inputs carry the draft prefix).  The two calls share the workspace; the
+    result equals the oracle's and, with the same head kernel, the fused call bit for bit."""
+    block = 16
+    W = synth.make_head(V, d, 8)
+    hd, ht = synth.make_hidden(B, K, d, 8, 0.8, 3.0 / (0.02 * np.sqrt(d)))
+    mask = synth.random_mask(B, block, 6, 3)
+    Wd, hdd, htd, md = W.to(DEV), hd.to(DEV), ht.to(DEV), torch.as_tensor(mask).to(DEV)
+    vs = fb.VerifyStep(B, K, block, d, V, device=DEV, diag=True, diag_logits=True, gemm_variant=variant)
+    vs.out_accept_len.fill_(-7)
+    tok, _, _ = vs(hdd, None, Wd, 8, step=3, mask_in=md, phase=fb.FEF_PHASE_DRAFT)
+    torch.cuda.synchronize()
+    drafts = _np(tok).copy()
+    assert np.all(_np(vs.out_accept_len) == -7)                # the draft call leaves it alone
+    tok, acc, rem = vs(None, htd, Wd, 8, step=3, mask_in=md, phase=fb.FEF_PHASE_TARGET)
+    torch.cuda.synchronize()
+    ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), synth.to_f64(W), K, block, 8, step=3, mask_in=mask,
+                        return_logits=True)
+    diag = {k: _np(v).copy() for k, v in vs.diag.items()}
+    st = parity.compare(ref, _np(tok), _np(acc), _np(rem), diag)
+    ok = ref.draft_gap >= parity.TOL_CDF
+    assert np.array_equal(drafts[ok], ref.draft_tokens[ok])
+    assert st["near_flipped"] <= B // 20
+    split = (_np(tok).copy(), _np(acc).copy(), _np(rem).copy(), diag["logits"], diag["alpha"])
+    # fused call through the kernel the split calls used
+    used = fb.fef_select_gemm(vs._params(), K) if variant != fb.FEF_GEMM_AUTO else None
+    p = vs._params(); p.phase = fb.FEF_PHASE_DRAFT
+    used = fb.fef_select_gemm(p, K)
+    if used != fb.FEF_GEMM_SKINNY or 2 * B * K <= 16:
+        vf = fb.VerifyStep(B, K, block, d, V, device=DEV, diag=True, diag_logits=True, gemm_variant=used)
+        tok2, acc2, rem2 = vf(hdd, htd, Wd, 8, step=3, mask_in=md)
+        torch.cuda.synchronize()
+        fused = (_np(tok2), _np(acc2), _np(rem2), _np(vf.diag["logits"]), _np(vf.diag["alpha"]))
+        for x, y in zip(split, fused):
+            assert np.array_equal(x, y)
