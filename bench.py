@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--split", action="store_true",
                     help="the method's own call order: a draft-only call, then a target-only call "
                          "(W is read twice); the roofline entry then describes the target call's head launch")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the 16 distinct steps once into a HIP graph and time its replays "
+                         "(the head-kernel events then come from a second, eager pass)")
     ap.add_argument("--events", choices=["inline", "separate"], default="inline",
                     help="record the head-kernel events inside the timed steps, or in a second pass")
     args = ap.parse_args()
@@ -132,7 +135,7 @@ def main():
     p0.phase = fb.FEF_PHASE_DRAFT if args.split else fb.FEF_PHASE_FUSED
     variant = fb.fef_select_gemm(p0, wl.K)
     ev = HipEvents()
-    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    pairs = [(ev.create(), ev.create()) for _ in range(max(args.steps, 16))]
 
     def step(i, events=None):
         hd, ht = rounds_d[i % n_rounds]
@@ -146,17 +149,37 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    inline = args.events == "inline"
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, pairs[i] if inline else None)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    inline = args.events == "inline" and not args.graph
+    if args.graph:
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            for i in range(n_rounds):
+                step(i)
+        replays = max(1, args.steps // n_rounds)
+        args.steps = replays * n_rounds
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    else:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i, pairs[i] if inline else None)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     if not inline:
         for i in range(args.steps):
             step(i, pairs[i])
         torch.cuda.synchronize()
-    head_ms = [ev.elapsed_ms(a, b) for a, b in pairs]
+    head_ms = [ev.elapsed_ms(a, b) for a, b in pairs[:args.steps]]
     head_avg_s = sum(head_ms) / len(head_ms) / 1e3
 
     ms_per_step = elapsed / args.steps * 1e3
@@ -177,7 +200,7 @@ def main():
                             fb.FEF_GEMM_TILED256: "head_tiled256_kernel",
                             fb.FEF_GEMM_F32: "head_f32_kernel"}[variant],
                  "avg_kernel_us": head_avg_s * 1e6, "algorithmic_bytes": hb, "flops": flops,
-                 "events": args.events})
+                 "events": "separate" if args.graph else args.events})
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
@@ -195,7 +218,8 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "K": wl.K, "block": wl.block, "d": wl.d, "V": wl.V,
                    "rho": wl.rho, "logit_std": wl.logit_std, "temperature": wl.temperature,
-                   "rows_through_head": M, "call_order": "draft+target" if args.split else "fused"},
+                   "rows_through_head": M, "call_order": "draft+target" if args.split else "fused",
+                   "launch": "hip graph replay" if args.graph else "stream"},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -5,6 +5,16 @@
 
 #include "fef_device.hpp"
 
+// Launch a head kernel; the dispatch-timestamp events need the extended launch call, every other
+// launch uses the plain one (which a capturing stream records like any kernel node).
+#define FEF_LAUNCH_HEAD(kernel, grid, block, a, ...)                                              \
+  do {                                                                                            \
+    if ((a).ev_begin || (a).ev_end)                                                               \
+      hipExtLaunchKernelGGL(kernel, grid, block, 0, (a).stream, (a).ev_begin, (a).ev_end, 0, __VA_ARGS__); \
+    else                                                                                          \
+      hipLaunchKernelGGL(kernel, grid, block, 0, (a).stream, __VA_ARGS__);                        \
+  } while (0)
+
 namespace fef {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));

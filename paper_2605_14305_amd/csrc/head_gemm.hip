@@ -294,16 +294,13 @@ hipError_t launch_head_skinny_nb(const HeadArgs& a) {
   const int grid = a.nT;  // = min(tiles, kSkinnyMaxGrid): one partial per (row, workgroup)
   switch (a.d) {
     case 512:
-      hipExtLaunchKernelGGL((head_skinny_kernel<2, NB>), dim3(grid), dim3(kSkinnyThreads), 0, a.stream,
-                            a.ev_begin, a.ev_end, 0, a, tiles);
+      FEF_LAUNCH_HEAD((head_skinny_kernel<2, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
       break;
     case 3584:
-      hipExtLaunchKernelGGL((head_skinny_kernel<14, NB>), dim3(grid), dim3(kSkinnyThreads), 0, a.stream,
-                            a.ev_begin, a.ev_end, 0, a, tiles);
+      FEF_LAUNCH_HEAD((head_skinny_kernel<14, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
       break;
     case 4096:
-      hipExtLaunchKernelGGL((head_skinny_kernel<16, NB>), dim3(grid), dim3(kSkinnyThreads), 0, a.stream,
-                            a.ev_begin, a.ev_end, 0, a, tiles);
+      FEF_LAUNCH_HEAD((head_skinny_kernel<16, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
       break;
     default:
       return hipErrorInvalidValue;
@@ -317,14 +314,12 @@ hipError_t launch_head_tiled(const HeadArgs& a) {
   const int M = a.nrows;
   const int m_tiles = (M + TM - 1) / TM, n_tiles = (a.V + TN - 1) / TN;
   const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
-  hipExtLaunchKernelGGL(head_tiled_kernel, dim3((unsigned)grid), dim3(kTiledThreads), 0, a.stream,
-                        a.ev_begin, a.ev_end, 0, a, m_tiles, n_tiles);
+  FEF_LAUNCH_HEAD(head_tiled_kernel, dim3((unsigned)grid), dim3(kTiledThreads), a, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 
 hipError_t launch_head_f32(const HeadArgs& a) {
-  hipExtLaunchKernelGGL(head_f32_kernel, dim3(a.nT, a.nrows), dim3(kWave), 0, a.stream, a.ev_begin,
-                        a.ev_end, 0, a);
+  FEF_LAUNCH_HEAD(head_f32_kernel, dim3(a.nT, a.nrows), dim3(kWave), a, a);
   return hipGetLastError();
 }
 

@@ -206,8 +206,7 @@ hipError_t launch_head_tiled256(const HeadArgs& a) {
   const int M = a.nrows;
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (a.V + BN - 1) / BN;
   const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
-  hipExtLaunchKernelGGL(head_tiled256_kernel<2>, dim3((unsigned)grid), dim3(512), 0, a.stream,
-                        a.ev_begin, a.ev_end, 0, a, m_tiles, n_tiles);
+  FEF_LAUNCH_HEAD(head_tiled256_kernel<2>, dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 
