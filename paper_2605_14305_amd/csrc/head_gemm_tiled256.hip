@@ -85,13 +85,15 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
     gp[q] = h_row(a, r) + c * 8;
     gp[QI + q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
   }
+  // load n (0 .. 2 QI - 1) of this wavefront for k-step kt: A rows first, then B rows
+  auto issue_one = [&](bf16x8* stage, int kt, int n) {
+    const int q = n % QI;
+    bf16x8* dst = stage + (n < QI ? 0 : BM * 4) + (wave * (16 * QI) + q * 16) * 4;
+    load_to_lds_16(gp[n] + kt * BK, lds_offset(dst));
+  };
   auto issue = [&](bf16x8* stage, int kt) {
-    const int k0 = kt * BK;
 #pragma unroll
-    for (int q = 0; q < QI; ++q) {
-      load_to_lds_16(gp[q] + k0, lds_offset(stage + (wave * (16 * QI) + q * 16) * 4));
-      load_to_lds_16(gp[QI + q] + k0, lds_offset(stage + BM * 4 + (wave * (16 * QI) + q * 16) * 4));
-    }
+    for (int n = 0; n < 2 * QI; ++n) issue_one(stage, kt, n);
   };
 
   floatx16 acc[4][TJ];
@@ -129,9 +131,21 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
     if (kt + 2 < nk) wait_newer<2 * QI>();
     else wait_newer<0>();
     lds_barrier();
-    if (kt + 3 < nk) issue(refill, kt + 3);
     read_frag(st_cur, 1, nxt);
-    mfma_frag(cur);
+    // The refill loads are spread between the multiplies: a wavefront issues in order, and eight
+    // wavefronts pushing all their loads right after the barrier fill the address FIFO and stall
+    // in front of their own MFMAs.
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (kt + 3 < nk && i < 2 * QI) issue_one(refill, kt + 3, i);
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int n = 4; n < 2 * QI; ++n)
+      if (kt + 3 < nk) issue_one(refill, kt + 3, n);
     if (kt + 1 < nk) read_frag(st_next, 0, cur);
     mfma_frag(nxt);
   };
