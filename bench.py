@@ -196,7 +196,8 @@ def main():
         ach = flops / head_avg_s / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
-    roof.update({"kernel": {fb.FEF_GEMM_SKINNY: "head_skinny_kernel", fb.FEF_GEMM_TILED: "head_tiled_kernel",
+    roof.update({"kernel": {fb.FEF_GEMM_SKINNY: "head_skinny_kernel" if M <= 16 else "head_skinny32_kernel",
+                            fb.FEF_GEMM_TILED: "head_tiled_kernel",
                             fb.FEF_GEMM_TILED256: "head_tiled256_kernel",
                             fb.FEF_GEMM_F32: "head_f32_kernel"}[variant],
                  "avg_kernel_us": head_avg_s * 1e6, "algorithmic_bytes": hb, "flops": flops,

@@ -69,7 +69,7 @@ typedef enum {
  * in this call: 2*B*K fused, B*K in a DRAFT or TARGET call. */
 typedef enum {
   FEF_GEMM_AUTO = 0,
-  FEF_GEMM_SKINNY = 1, /* bf16, M <= 16, d in {512, 3584, 4096}: W streamed once, split-k  */
+  FEF_GEMM_SKINNY = 1, /* bf16, M <= 32, d in {512, 3584, 4096}: W streamed once, split-k  */
   FEF_GEMM_TILED = 2,  /* bf16, any M: 128x128 LDS-tiled MFMA GEMM (AUTO: M <= 128)        */
   FEF_GEMM_F32 = 3,    /* f32, any shape: reference-grade FMA kernel                       */
   FEF_GEMM_TILED256 = 4 /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)        */

@@ -4,7 +4,8 @@
 // logits written once, and per (row, vocabulary tile) partials (max, sum exp(L - max)) from
 // which the row's log-sum-exp is merged later.
 //
-//   head_skinny_kernel  M = 2*B*K <= 16.  HBM-bound: W (about 1 GB) is streamed exactly once.
+//   head_skinny_kernel  M = 2*B*K <= 16 (head_skinny32_kernel: 16 < M <= 32, see there).
+//                       HBM-bound: W (about 1 GB) is streamed exactly once.
 //                       One workgroup per CU owns a contiguous run of 16-token tiles.  Its
 //                       eight wavefronts split k; each keeps its slice of H in registers as
 //                       the MFMA B operand for the whole kernel, streams its 1 KB slice of
@@ -34,12 +35,13 @@ constexpr int kSkinnyThreads = kSkinnyWaves * kWave;
 // NB = tiles accumulated in registers between two cross-wavefront reductions (even).
 template <int KS, int NB>
 __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a, int tiles_total) {
+  static_assert(NB * 64 <= kSkinnyThreads, "one reduction item per thread at most");
   __shared__ floatx4 red[2][NB][kSkinnyWaves][kWave];
-  __shared__ float2 run_merge[kSkinnyThreads / 16];
+  __shared__ float2 run_merge[NB][16];
   // Logits of this workgroup's tokens wait here and leave in one coalesced burst: a global
   // store inside the streaming loop would share the vector-memory counter with the W
   // prefetch and force every wait on a W tile to drain the tiles fetched ahead as well.
-  __shared__ float out[16][kSkinnyOutTiles * 16 + 4];
+  __shared__ __attribute__((aligned(16))) float out[16][kSkinnyOutTiles * 16 + 16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, g = lane >> 4;
   const int M = a.nrows;
@@ -75,10 +77,12 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
     return acc;
   };
 
-  // Output element of this thread inside a batch: row m, token vl of tile (tid >> 8) + 2 q.
-  const int m = (tid >> 4) & 15, vl = tid & 15;
-  const int src = m + 16 * (vl >> 2), comp = vl & 3;
-  // running (max, sum exp) over this thread's tiles, replicated over the row's 16 lanes
+  // Reduction item of this thread inside a batch (threads 0..64 NB - 1): tile jt_o of the
+  // batch, row m, tokens 4 quad .. 4 quad + 3.  The D layout puts exactly those four sums in
+  // lane m + 16 quad of every wavefront's accumulator.
+  const int jt_o = tid >> 6, m = (tid >> 2) & 15, quad = tid & 3;
+  const int src = m + 16 * quad;
+  // running (max, sum exp) over this thread's tiles, replicated over the item's 4 lanes
   float run_m = -INFINITY, run_s = 0.f;
 
   bf16x8 buf0[KS], buf1[KS];
@@ -104,27 +108,28 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
     for (int i = 0; i < NB; ++i)
       if (i < nb) red[par][i][wave][lane] = acc[i];
     lds_barrier();
-    // sum the eight k-slices in wave order; 512 threads cover two tiles per pass
+    // sum the eight k-slices in wave order
+    if (jt_o < nb) {
+      floatx4 sum = red[par][jt_o][0][src];
 #pragma unroll
-    for (int q = 0; q < NB / 2; ++q) {
-      const int jt = (tid >> 8) + 2 * q;
-      if (jt < nb) {
-        float sum = 0.f;
+      for (int w = 1; w < kSkinnyWaves; ++w) sum += red[par][jt_o][w][src];
+      sum *= a.inv_tau;
+      const int v = (t + jt_o) * 16 + 4 * quad;
+      *reinterpret_cast<floatx4*>(&out[m][(t + jt_o - tflush) * 16 + 4 * quad]) = sum;
+      float mx = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kSkinnyWaves; ++w) sum += red[par][jt][w][src][comp];
-        const float logit = sum * a.inv_tau;
-        const int v = (t + jt) * 16 + vl;
-        const bool valid = v < a.V && m < M;
-        out[m][(t + jt - tflush) * 16 + vl] = logit;
-        float mx = valid ? logit : -INFINITY;
+      for (int c = 0; c < 4; ++c)
+        if (v + c < a.V && m < M) mx = fmaxf(mx, sum[c]);
+      mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+      float e = 0.f;
 #pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-        float e = valid ? __expf(logit - mx) : 0.f;
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) e += __shfl_xor(e, off, 64);
-        if (mx > run_m) { run_s = run_s * __expf(run_m - mx) + e; run_m = mx; }
-        else if (mx > -INFINITY) run_s += e * __expf(mx - run_m);
-      }
+      for (int c = 0; c < 4; ++c)
+        if (v + c < a.V && m < M) e += __expf(sum[c] - mx);
+      e += __shfl_xor(e, 1, 64);
+      e += __shfl_xor(e, 2, 64);
+      if (mx > run_m) { run_s = run_s * __expf(run_m - mx) + e; run_m = mx; }
+      else if (mx > -INFINITY) run_s += e * __expf(mx - run_m);
     }
     par ^= 1;
     if (t + NB - tflush + NB > kSkinnyOutTiles || t + NB >= t1) {
@@ -139,15 +144,148 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
     }
   }
 
-  // merge the two threads that share a row (tid and tid + 256) and write the workgroup's partial
-  if (vl == 0) run_merge[tid >> 4] = make_float2(run_m, run_s);
+  // merge the NB items that share a row and write the workgroup's partial
+  if (quad == 0 && jt_o < NB) run_merge[jt_o][m] = make_float2(run_m, run_s);
   __syncthreads();
   if (tid < 16 && tid < M) {
-    const float2 p0 = run_merge[tid], p1 = run_merge[tid + 16];
-    const float mx = fmaxf(p0.x, p1.x);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) mx = fmaxf(mx, run_merge[j][tid].x);
     float sm = 0.f;
-    if (p0.x > -INFINITY) sm += p0.y * __expf(p0.x - mx);
-    if (p1.x > -INFINITY) sm += p1.y * __expf(p1.x - mx);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const float2 pj = run_merge[j][tid];
+      if (pj.x > -INFINITY) sm += pj.y * __expf(pj.x - mx);
+    }
+    a.partials[(size_t)tid * a.nT + blockIdx.x] = make_float2(mx, sm);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Skinny kernel for 16 < M <= 32 (a 16-token window at B = 1, or two 8-token windows): the same
+// streaming scheme with two 16-row groups of H resident per wavefront (2 * KS operand
+// registers), each W tile multiplied against both.  The register budget then leaves room for
+// one W buffer only: the next tile's loads are issued right after the multiplies that consumed
+// the current one, which keeps one 16 KB tile per wavefront (128 KB per CU) in flight.
+// The reduction buffer is single (two barriers per batch) so that it and the 32-row logits
+// staging fit in LDS together.
+// ---------------------------------------------------------------------------------------------
+template <int KS, int NB>
+__global__ __launch_bounds__(kSkinnyThreads) void head_skinny32_kernel(HeadArgs a, int tiles_total) {
+  static_assert(NB * 128 == kSkinnyThreads, "one reduction item per thread");
+  __shared__ floatx4 red[NB][2][kSkinnyWaves][kWave];
+  __shared__ float2 run_merge[NB][32];
+  __shared__ __attribute__((aligned(16))) float out[32][kSkinnyOutTiles * 16 + 16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, g = lane >> 4;
+  const int M = a.nrows;
+  const int kofs = wave * (KS * 32) + g * 8;
+
+  bf16x8 hreg[2][KS];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt) {
+    const int r = mt * 16 + i16;
+    const bool live = r < M;
+    const __bf16* hp = h_row(a, live ? r : 0) + kofs;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      bf16x8 v = *reinterpret_cast<const bf16x8*>(hp + 32 * s);
+      if (!live) v = bf16x8{};
+      hreg[mt][s] = v;
+    }
+  }
+
+  const int t0 = (int)((long)blockIdx.x * tiles_total / gridDim.x);
+  const int t1 = (int)((long)(blockIdx.x + 1) * tiles_total / gridDim.x);
+  const __bf16* Wl = (const __bf16*)a.W + kofs;
+
+  bf16x8 buf[KS];
+  auto load_tile = [&](int t) {
+    const int v = min(t * 16 + i16, a.V - 1);
+    const __bf16* wp = Wl + (size_t)v * a.d;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) buf[s] = *reinterpret_cast<const bf16x8*>(wp + 32 * s);
+  };
+
+  // Reduction item of this thread inside a batch: tile jt_o, row group mt_o, row m of it,
+  // tokens 4 quad .. 4 quad + 3 (64 NB * 2 items; NB = 4 gives every thread one).
+  const int jt_o = tid >> 7, mt_o = (tid >> 6) & 1, m = (tid >> 2) & 15, quad = tid & 3;
+  const int row = mt_o * 16 + m;
+  const int src = m + 16 * quad;
+  float run_m = -INFINITY, run_s = 0.f;
+
+  floatx4 acc[NB][2];
+  int tflush = t0;
+  if (t0 < t1) load_tile(t0);
+  for (int t = t0; t < t1; t += NB) {
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      if (t + i < t1) {
+        floatx4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[s], hreg[0][s], c0, 0, 0, 0);
+          c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[s], hreg[1][s], c1, 0, 0, 0);
+        }
+        acc[i][0] = c0;
+        acc[i][1] = c1;
+        if (t + i + 1 < t1) load_tile(t + i + 1);
+      }
+    }
+    const int nb = min(NB, t1 - t);
+    lds_barrier();  // every thread has finished reading the previous batch
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      if (i < nb) {
+        red[i][0][wave][lane] = acc[i][0];
+        red[i][1][wave][lane] = acc[i][1];
+      }
+    lds_barrier();
+    if (jt_o < nb) {
+      floatx4 sum = red[jt_o][mt_o][0][src];
+#pragma unroll
+      for (int w = 1; w < kSkinnyWaves; ++w) sum += red[jt_o][mt_o][w][src];
+      sum *= a.inv_tau;
+      const int v = (t + jt_o) * 16 + 4 * quad;
+      *reinterpret_cast<floatx4*>(&out[row][(t + jt_o - tflush) * 16 + 4 * quad]) = sum;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (v + c < a.V && row < M) mx = fmaxf(mx, sum[c]);
+      mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+      float e = 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (v + c < a.V && row < M) e += __expf(sum[c] - mx);
+      e += __shfl_xor(e, 1, 64);
+      e += __shfl_xor(e, 2, 64);
+      if (mx > run_m) { run_s = run_s * __expf(run_m - mx) + e; run_m = mx; }
+      else if (mx > -INFINITY) run_s += e * __expf(mx - run_m);
+    }
+    if (t + NB - tflush + NB > kSkinnyOutTiles || t + NB >= t1) {
+      const int tend = min(t + NB, t1);
+      const int v0 = tflush * 16, nv = min(tend * 16, a.V) - v0;
+      __syncthreads();
+      for (int r = wave; r < M; r += kSkinnyWaves)
+        for (int i = lane; i < nv; i += kWave) a.logits[(size_t)r * a.ldl + v0 + i] = out[r][i];
+      __syncthreads();
+      tflush = tend;
+    }
+  }
+  // merge the NB items that share a row and write the workgroup's partial
+  if (quad == 0) run_merge[jt_o][row] = make_float2(run_m, run_s);
+  __syncthreads();
+  if (tid < 32 && tid < M) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) mx = fmaxf(mx, run_merge[j][tid].x);
+    float sm = 0.f;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const float2 pj = run_merge[j][tid];
+      if (pj.x > -INFINITY) sm += pj.y * __expf(pj.x - mx);
+    }
     a.partials[(size_t)tid * a.nT + blockIdx.x] = make_float2(mx, sm);
   }
 }
@@ -286,12 +424,28 @@ __global__ __launch_bounds__(kWave) void head_f32_kernel(HeadArgs a) {
 
 }  // namespace
 
-bool skinny_supports(int M, int d) { return M <= 16 && (d == 512 || d == 3584 || d == 4096); }
+bool skinny_supports(int M, int d) { return M <= 32 && (d == 512 || d == 3584 || d == 4096); }
 
 template <int NB>
 hipError_t launch_head_skinny_nb(const HeadArgs& a) {
   const int tiles = (a.V + kSkinnyUnit - 1) / kSkinnyUnit;
   const int grid = a.nT;  // = min(tiles, kSkinnyMaxGrid): one partial per (row, workgroup)
+  if (a.nrows > 16) {
+    switch (a.d) {
+      case 512:
+        FEF_LAUNCH_HEAD((head_skinny32_kernel<2, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
+        break;
+      case 3584:
+        FEF_LAUNCH_HEAD((head_skinny32_kernel<14, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
+        break;
+      case 4096:
+        FEF_LAUNCH_HEAD((head_skinny32_kernel<16, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
+        break;
+      default:
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (a.d) {
     case 512:
       FEF_LAUNCH_HEAD((head_skinny_kernel<2, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);

@@ -47,6 +47,8 @@ WORKLOADS = {
                         rho=0.9, logit_std=0.0),
     "llada_b1": Workload("llada_b1", B=1, K=8, block=32, gen_len=256, d=4096, V=126464,
                          dtype="bf16", rho=0.9, logit_std=3.0),
+    "llada_k16": Workload("llada_k16", B=1, K=16, block=32, gen_len=256, d=4096, V=126464,
+                          dtype="bf16", rho=0.9, logit_std=3.0),
     "llada_b2": Workload("llada_b2", B=2, K=8, block=32, gen_len=256, d=4096, V=126464,
                          dtype="bf16", rho=0.9, logit_std=3.0),
     "llada_b4": Workload("llada_b4", B=4, K=8, block=32, gen_len=256, d=4096, V=126464,

@@ -53,7 +53,9 @@ def test_workspace_size_scales(lib):
 def test_gemm_selection(lib):
     assert fb.fef_select_gemm(fb.make_params(1, 4096, 126464), 8) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(1, 3584, 151936), 8) == fb.FEF_GEMM_SKINNY
-    assert fb.fef_select_gemm(fb.make_params(1, 4096, 126464), 16) == fb.FEF_GEMM_TILED
+    assert fb.fef_select_gemm(fb.make_params(1, 4096, 126464), 16) == fb.FEF_GEMM_SKINNY
+    assert fb.fef_select_gemm(fb.make_params(2, 4096, 126464), 8) == fb.FEF_GEMM_SKINNY
+    assert fb.fef_select_gemm(fb.make_params(3, 4096, 126464), 8) == fb.FEF_GEMM_TILED
     assert fb.fef_select_gemm(fb.make_params(16, 4096, 126464), 8) == fb.FEF_GEMM_TILED256
     assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_TILED
     assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_TILED

@@ -92,6 +92,35 @@ def test_skinny_kernel_small_shapes(K, V):
     assert near == 0
 
 
+@pytest.mark.parametrize("B,K,V", [(1, 16, 1000), (2, 8, 4099), (3, 5, 16), (1, 9, 7), (2, 7, 10300)])
+def test_skinny_kernel_two_row_groups(B, K, V):
+    """17..32 rows through the head: the streaming kernel with two resident 16-row groups."""
+    near = 0
+    for step in range(3):
+        ref, out, st = run_case(B, K, 16, 512, V, seed=15, rho=0.8, step=step, variant=fb.FEF_GEMM_SKINNY)
+        near += st["near_flipped"]
+    assert near == 0
+
+
+def test_window_16_batch1_full_size(llada_head):
+    """LLaDA-shaped head with a 16-token window at batch 1 (32 rows through the head), every
+    output element against the oracle."""
+    wl, W, Wd, W64 = llada_head
+    K, block = 16, 32
+    vs = fb.VerifyStep(1, K, block, wl.d, wl.V, device=DEV, diag=True, diag_logits=True)
+    assert fb.fef_select_gemm(vs._params(), K) == fb.FEF_GEMM_SKINNY
+    near = compared = 0
+    for step in range(2):
+        hd, ht = synth.make_hidden(1, K, wl.d, 4, wl.rho, wl.sigma_h, "bf16", 0, step)
+        tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 4, step=step)
+        torch.cuda.synchronize()
+        ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), W64, K, block, 4, step=step, return_logits=True)
+        st = parity.compare(ref, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs.diag.items()})
+        near += st["near_flipped"]; compared += st["equal"]
+        print(f"step {step}: accept_len {ref.accept_len[0]} {st}", flush=True)
+    assert compared >= 1 and near <= 1
+
+
 @pytest.mark.parametrize("B,K,d,V", [(5, 8, 64, 1000), (20, 8, 512, 777), (3, 16, 3584, 2050),
                                      (70, 2, 128, 300), (1, 1, 64, 1)])
 def test_tiled_kernel_small_shapes(B, K, d, V):
