@@ -16,8 +16,12 @@ LowConf inside the round that resolves the block, so the while-loop of pass s en
 and the next pass starts from the re-masked positions.  Re-corrupted positions hold MASK (-1)
 in X until they are committed again.
 
+With recorrupt_prob < 1 a selected position returns to MASK only with that probability; a pass whose
+selection re-corrupts nothing has no unresolved position, so its while-loop and those of all later
+passes run zero rounds and X is final.
+
 Pinned in tests: every position is committed exactly once per pass it belongs to, pass s >= 1
-re-resolves exactly min(n_rm, candidates) positions, the number of rounds of a pass is at least
+re-resolves exactly min(n_rm, candidates) positions (recorrupt_prob = 1), the number of rounds of a pass is at least
 ceil(L / k), the final X has no MASK, and a run with N_step = 1 equals chaining verify_step by
 hand.
 """
@@ -42,7 +46,7 @@ class DecodeResult:
 
 
 def decode_block(hidden, W, B, K, block, seed, n_pass, n_rm=-1, temperature=1.0, seq_base=0,
-                 pos_base=0, step_base=0, lowconf_scope=0, max_rounds=None):
+                 pos_base=0, step_base=0, lowconf_scope=0, max_rounds=None, recorrupt_prob=1.0):
     W = np.asarray(W, dtype=np.float64)
     X = np.full((B, block), MASK, np.int64)
     conf_out = np.zeros((B, block))
@@ -67,7 +71,7 @@ def decode_block(hidden, W, B, K, block, seed, n_pass, n_rm=-1, temperature=1.0,
                 res = O.verify_step(hd[b:b + 1], ht[b:b + 1], W, K, block, seed, temperature=temperature,
                                     step=step_base + r, seq_base=seq_base + b, pos_base=pos_base, n_rm=n_rm,
                                     final_pass=(s == n_pass - 1), lowconf_scope=lowconf_scope,
-                                    mask_in=mask, pass_mask=pmask, conf=conf)
+                                    mask_in=mask, pass_mask=pmask, conf=conf, recorrupt_prob=recorrupt_prob)
                 C = int(res.committed[0])
                 for m in range(C):
                     X[b, res.slot_pos[0, m]] = res.tokens[0, m]

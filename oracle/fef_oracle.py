@@ -6,8 +6,8 @@ call this.  It shares no code with the HIP path.  Every function is pinned by th
 suite against identities the paper proves (one-step identity in the proof of Theorem 1, the
 residual-distribution equation, Theorem 2), library routines, brute force on tiny inputs and
 the published Philox known-answer vectors.  Not pinned ("parity unpinned"): nothing that is
-implemented here; the stochastic re-corruption variant, classifier-free guidance and greedy
-(temperature 0) verification are not implemented at all.
+implemented here; classifier-free guidance and greedy (temperature 0) verification are not
+implemented at all.
 
 Notation follows the paper: rho / q = draft law, pi / p = target law, k = window, x~ = draft
 token, C = committed positions, alpha = sum_v min(p_v, q_v).
@@ -28,8 +28,9 @@ sequences; all sequences are vectorised with numpy, the window is an explicit lo
       on the first rejection sample Z ~ pi' = [pi - rho]_+ / (1 - sum min{pi, rho})
       (residual-distribution equation), commit Z with confidence pi(Z), discard the rest.
   S6  when no unresolved position is left in the block and this is not the final pass:
-      R = LowConf_{n_rm}(C^(s)) and the selected positions return to the corrupted state
-      (absorbing kernel: they become MASK again).
+      R = LowConf_{n_rm}(C^(s)) and every selected position is re-corrupted through the
+      absorbing forward kernel q(X_t^i | X_0^i): MASK with probability recorrupt_prob
+      (= 1 - alpha-bar_t of that kernel; 1 by default), otherwise it keeps its token.
 
 Readings of points the paper leaves open are listed with each function.
 """
@@ -148,10 +149,28 @@ def low_confidence(conf_row, candidates, n_rm):
     return order[:n], gap
 
 
+def recorrupt(selected, prob, seed, pos_base, step, sequence):
+    """Algorithm 2, "Re-corrupt X^i ~ q(X_t^i | X_0^i)" with the absorbing (mask) forward
+    kernel of D3PM: position i becomes MASK with probability prob = 1 - alpha-bar_t and keeps
+    its clean token otherwise, independently over positions.  Returns the positions that
+    become MASK.
+
+    Readings: the paper gives neither t nor the uniforms.  prob is an input (a binary32 number,
+    as the boundary carries it; 1 reproduces "selected positions always return to MASK"); the
+    draw for position i is Philox stream 3 at (absolute position, step, sequence) and the
+    position is masked iff u < prob, both exact in binary32 and binary64."""
+    selected = np.asarray(selected, dtype=np.int64)
+    p = float(np.float32(prob))
+    if p >= 1.0 or selected.size == 0:
+        return selected
+    u = philox.uniform(seed, pos_base + selected, step, sequence, philox.STREAM_RECORRUPT)
+    return selected[u < p]
+
+
 def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0,
                 seq_base=0, pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0,
                 mask_in=None, pass_mask=None, conf=None, draft_tokens=None,
-                return_logits=False):
+                return_logits=False, recorrupt_prob=1.0):
     """One speculative round for B sequences.
 
     h_draft, h_target: [B,K,d] float64 (row m belongs to window slot m); W: [V,d] float64.
@@ -167,7 +186,7 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
         position is committed too and there is no extra token after a fully accepted window
         (Theorem 2: C_k <= k).
       * re-corruption is the absorbing kernel: a selected position becomes MASK with
-        probability one.  n_rm < 0 means block // 2.
+        probability recorrupt_prob (see recorrupt()).  n_rm < 0 means block // 2.
       * LowConf ranges over the positions committed in the current pass (lowconf_scope 0,
         the literal C^(s)) or over every position of the resolved block (scope 1).
       * a rejection that meets residual mass <= 0 (cannot happen in exact arithmetic)
@@ -280,7 +299,7 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
                 continue
             cand = pmask[b] if lowconf_scope == 0 else np.ones(block, np.uint8)
             sel, lowconf_gap[b] = low_confidence(cf[b], cand, n_rm)
-            new_mask[b, sel] = 1
+            new_mask[b, recorrupt(sel, recorrupt_prob, seed, pos_base, step, seq_base + b)] = 1
             pmask[b, :] = 0
 
     return StepResult(tokens=tokens, accept_len=accept_len, committed=committed,

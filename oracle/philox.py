@@ -10,8 +10,9 @@ way:
     key     = (seed low 32 bits, seed high 32 bits)
     counter = (position, step, sequence, stream)
 
-and use output word 0 only.  ``stream`` separates the three draws of a speculative round:
-0 = draft-token sample, 1 = accept-test uniform, 2 = residual sample.
+and use output word 0 only.  ``stream`` separates the draws of a speculative round:
+0 = draft-token sample, 1 = accept-test uniform, 2 = residual sample, 3 = re-corruption of a
+low-confidence position (Algorithm 2, "Re-corrupt").
 
 A 32-bit word w becomes the uniform  u = ((w >> 9) + 1/2) * 2**-23 : 2**23 equally spaced
 values strictly inside (0,1), each exactly representable in fp32 as well as fp64 (odd
@@ -31,6 +32,7 @@ _SHIFT32 = np.uint64(32)
 STREAM_DRAFT = 0
 STREAM_ACCEPT = 1
 STREAM_RESIDUAL = 2
+STREAM_RECORRUPT = 3
 
 
 def philox4x32_10(counter, key):
