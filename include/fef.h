@@ -12,15 +12,18 @@
  *   correct     Z ~ [pi - rho]_+ / (1 - sum_z min{pi, rho})   (residual-distribution equation)
  *   commit      token and confidence c = pi(token) for accepted slots and the corrected one
  *   re-mask     if no unresolved position is left and this is not the final pass:
- *               the n_rm committed positions of the pass with the lowest confidence return to
- *               the corrupted (MASK) state
+ *               the n_rm committed positions of the pass with the lowest confidence are
+ *               re-corrupted through the absorbing forward kernel: each returns to the MASK
+ *               state with probability recorrupt_prob (1 by default) and keeps its token
+ *               otherwise ("Re-corrupt X^i ~ q(X_t^i | X_0^i)")
  *
  * The model forwards that produce the hidden states are outside the library.  The vocabulary
  * head W is shared by both laws (the paper instantiates draft and target with one network).
  *
  * All random draws come from Philox4x32-10, key = (seed low, seed high), counter =
  * (pos_base + block offset of the slot, step, seq_base + b, stream), output word 0,
- * stream 0 = draft sample, 1 = accept test, 2 = residual sample; a word w becomes
+ * stream 0 = draft sample, 1 = accept test, 2 = residual sample, 3 = re-corruption of a
+ * selected position (masked iff u < recorrupt_prob); a word w becomes
  * u = ((w >> 9) + 0.5) * 2^-23.  A call is therefore a pure function of its arguments.
  *
  * Conventions
@@ -50,7 +53,7 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 2
+#define FEF_ABI_VERSION 3
 
 typedef enum {
   FEF_OK = 0,
@@ -132,6 +135,12 @@ typedef struct {
                                   are written at their positions, re-masked positions get -1   */
   int32_t phase;               /* fef_phase: the call order of the method when the target
                                   forward needs the draft tokens (see fef_phase)              */
+  float recorrupt_prob;        /* in (0, 1]: probability 1 - alpha-bar_t with which a position
+                                  selected by LowConf returns to MASK (absorbing forward kernel
+                                  of Algorithm 2's re-corruption step); 1 = always.  With
+                                  seq_pass, a selection that re-corrupts nothing leaves no
+                                  unresolved position for any later pass: the sequence is
+                                  marked done (s = n_pass)                                     */
 } fef_params;
 
 /* Bytes of device workspace a call with these sizes needs (depends on B, d, V, dtype,

@@ -49,6 +49,8 @@ fef_status check_sizes(const fef_params* p, int32_t K, int32_t block) {
     return fail(FEF_ERR_INVALID_ARG, "B*K = %ld exceeds 2^24 rows per call", (long)p->B * K);
   if (p->lowconf_scope != 0 && p->lowconf_scope != 1)
     return fail(FEF_ERR_INVALID_ARG, "lowconf_scope must be 0 or 1");
+  if (!(p->recorrupt_prob > 0.f && p->recorrupt_prob <= 1.f))
+    return fail(FEF_ERR_INVALID_ARG, "recorrupt_prob must lie in (0, 1]");
   if (p->phase != FEF_PHASE_FUSED && p->phase != FEF_PHASE_DRAFT && p->phase != FEF_PHASE_TARGET)
     return fail(FEF_ERR_INVALID_ARG, "unknown phase %d", p->phase);
   if (p->seq_pass && p->n_pass < 1)
@@ -204,6 +206,7 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   v.tile_unit = L.tile_unit; v.tile_T = L.tile_T; v.tile_G = L.nT;
   v.seed = seed; v.step = prm->step; v.seq_base = prm->seq_base; v.pos_base = prm->pos_base;
   v.n_rm = prm->n_rm; v.final_pass = prm->final_pass; v.lowconf_scope = prm->lowconf_scope;
+  v.recorrupt_prob = prm->recorrupt_prob;
   v.mask_in = prm->mask_in; v.pass_mask = prm->pass_mask; v.conf = prm->conf;
   v.draft_tokens_in = prm->draft_tokens;
   v.n_pass = prm->n_pass; v.seq_pass = prm->seq_pass; v.seq_rounds = prm->seq_rounds;

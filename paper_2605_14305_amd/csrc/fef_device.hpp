@@ -14,7 +14,7 @@ constexpr int kMaxK = 64;        // window (FEF_MAX_K): one ballot covers a wind
 // Philox4x32-10 (Salmon et al., SC'11).  key = (seed lo, seed hi); counter = (position, step,
 // sequence, stream); word 0 of the output is used.
 // ---------------------------------------------------------------------------------------------
-constexpr uint32_t kStreamDraft = 0, kStreamAccept = 1, kStreamResidual = 2;
+constexpr uint32_t kStreamDraft = 0, kStreamAccept = 1, kStreamResidual = 2, kStreamRecorrupt = 3;
 
 __host__ __device__ inline uint32_t philox_word0(uint64_t seed, uint32_t c0, uint32_t c1,
                                                  uint32_t c2, uint32_t c3) {
@@ -95,6 +95,7 @@ struct VerifyArgs {
   uint64_t seed;
   uint32_t step, seq_base, pos_base;
   int n_rm, final_pass, lowconf_scope;
+  float recorrupt_prob;
   const uint8_t* mask_in;
   uint8_t* pass_mask;
   float* conf;

@@ -495,6 +495,7 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
 
   const bool final = a.seq_pass ? a.seq_pass[b] >= a.n_pass - 1 : a.final_pass != 0;
   const bool fire = !unresolved && !final;
+  int remasked = 0;
   if (fire) {
     // LowConf: rank every candidate by (confidence, position); the n_rm lowest are re-masked
     const int n_rm = a.n_rm < 0 ? a.block / 2 : a.n_rm;
@@ -508,9 +509,19 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
         const float cj = s_conf[j];
         rank += (cand_j && (cj < ci || (cj == ci && j < i))) ? 1 : 0;
       }
-      if (rank < n_rm) s_mask[i] = 1;
+      if (rank < n_rm) {
+        // absorbing forward kernel: back to MASK with probability recorrupt_prob, else the
+        // position keeps its token (both sides of u < prob are exact binary32 numbers)
+        bool to_mask = true;
+        if (a.recorrupt_prob < 1.f)
+          to_mask = philox_uniform(a.seed, a.pos_base + (uint32_t)i, a.step, a.seq_base + (uint32_t)b,
+                                   kStreamRecorrupt) < a.recorrupt_prob;
+        if (to_mask) s_mask[i] = 1;
+      }
     }
     __syncthreads();
+    for (int i = tid; i < a.block; i += NT) remasked |= s_mask[i];
+    remasked = block_max_int(remasked, tmp);
   }
   if (a.tokens_state && tid < committed)
     a.tokens_state[row + a.slot_pos[b * a.K + tid]] = tid < acc_len ? st.x[tid] : z;
@@ -523,8 +534,8 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
   }
   if (tid == 0) {
     if (a.seq_pass) {
-      if (fire) a.seq_pass[b] += 1;
-      else if (!unresolved && final) a.seq_pass[b] = a.n_pass;
+      if (fire && remasked) a.seq_pass[b] += 1;
+      else if (!unresolved) a.seq_pass[b] = a.n_pass;  // final pass resolved, or nothing left to redo
     }
     if (a.seq_rounds && window > 0) a.seq_rounds[b] += 1;
   }

@@ -21,7 +21,7 @@ def _np(t):
 def run_case(B, K, block, d, V, dtype="bf16", seed=0, rho=0.9, logit_std=3.0, variant=fb.FEF_GEMM_AUTO,
              temperature=1.0, step=0, seq_base=0, pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0,
              mask=None, pass_mask=None, conf=None, draft_tokens=None, with_logits=True, W=None,
-             hidden=None, logit_atol=2e-4):
+             hidden=None, logit_atol=2e-4, recorrupt_prob=1.0):
     wl_sigma = logit_std / (0.02 * np.sqrt(d)) if logit_std > 0 else 1.0
     if W is None:
         W = synth.make_head(V, d, seed, dtype)
@@ -34,13 +34,13 @@ def run_case(B, K, block, d, V, dtype="bf16", seed=0, rho=0.9, logit_std=3.0, va
     tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), W.to(DEV), seed, temperature=temperature, step=step,
                        seq_base=seq_base, pos_base=pos_base, n_rm=n_rm, final_pass=final_pass,
                        lowconf_scope=lowconf_scope, mask_in=g_mask, pass_mask=g_pm, conf=g_cf,
-                       draft_tokens=g_dt)
+                       draft_tokens=g_dt, recorrupt_prob=recorrupt_prob)
     torch.cuda.synchronize()
     ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), synth.to_f64(W), K, block, seed,
                         temperature=temperature, step=step, seq_base=seq_base, pos_base=pos_base,
                         n_rm=n_rm, final_pass=final_pass, lowconf_scope=lowconf_scope, mask_in=mask,
                         pass_mask=pass_mask, conf=None if conf is None else np.asarray(conf, np.float32),
-                        draft_tokens=draft_tokens, return_logits=with_logits)
+                        draft_tokens=draft_tokens, return_logits=with_logits, recorrupt_prob=recorrupt_prob)
     diag = {k: _np(v) for k, v in vs.diag.items()}
     stats = parity.compare(ref, _np(tok), _np(acc), _np(rem), diag, drafts_given=draft_tokens is not None,
                            logit_atol=logit_atol)
@@ -224,6 +224,27 @@ def test_low_confidence_remask_fires_when_block_resolves(scope):
     ref, out, st = run_case(B, K, block, d, V, seed=41, rho=0.9, mask=mask, pass_mask=pm, conf=conf,
                             n_rm=3, lowconf_scope=scope, final_pass=True)
     assert np.all(out["remask"] <= mask)
+
+
+def test_stochastic_recorruption_of_the_low_confidence_selection():
+    """Re-corruption through the absorbing kernel with probability < 1: the re-masked set is the
+    oracle's (a subset of LowConf's selection chosen by Philox stream 3), everything else as before."""
+    B, K, block, d, V = 16, 4, 8, 512, 500
+    rng = np.random.default_rng(6)
+    mask = np.zeros((B, block), np.uint8)
+    mask[:, 5] = 1                                       # one position left: this round resolves the block
+    pm = np.ones((B, block), np.uint8) - mask
+    conf = rng.random((B, block)).astype(np.float32)
+    counts = {}
+    for prob in (1.0, 0.7, 0.3, 5e-8):
+        ref, out, st = run_case(B, K, block, d, V, seed=43, rho=0.9, mask=mask, pass_mask=pm, conf=conf,
+                                n_rm=6, recorrupt_prob=prob, step=3, pos_base=64, seq_base=5)
+        assert st["near_flipped"] == 0 and st["remask_skipped"] == 0
+        _check_state(ref, out)
+        assert np.array_equal(out["remask"], ref.remask)
+        counts[prob] = int(out["remask"].sum())
+    assert counts[1.0] == 6 * B and counts[5e-8] == 0
+    assert counts[1.0] > counts[0.7] > counts[0.3] > 0
 
 
 def test_stateful_pass_over_a_block_matches_oracle():
