@@ -52,6 +52,11 @@ __device__ inline float row16_max(float x) {
   x = fmaxf(x, row_ror<2>(x)); x = fmaxf(x, row_ror<1>(x));
   return x;
 }
+// Value of lane l ^ 16 (the other 16-lane row of the same 32-lane half): ds_swizzle in bit mode,
+// and_mask 0x1f, or_mask 0, xor_mask 0x10.  Uses the LDS crossbar, no LDS memory.
+__device__ inline float swap16(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0x401F));
+}
 __device__ inline float row16_sum(float x) {
   x += row_ror<8>(x); x += row_ror<4>(x); x += row_ror<2>(x); x += row_ror<1>(x);
   return x;

@@ -12,9 +12,9 @@
 // every bank once.  The permutation is applied on the global side (each lane fetches the chunk
 // that belongs in its LDS slot).
 //
-// The epilogue stages each 32 x 64 block of logits through LDS so that rows leave as 256-byte
-// coalesced stores and the per-row (max, sum exp) over the wavefront's 64 tokens is reduced
-// inside DPP rows of 16 lanes.
+// The epilogue works straight from the accumulator registers: for a fixed accumulator index the 32
+// lanes of a half-wavefront hold 32 consecutive tokens of one row, so dword stores write whole
+// 128-byte lines, and the per-row (max, sum exp) over the wavefront's 64 tokens is reduced by DPP.
 //
 // Tile order: workgroup ids go round-robin over the 8 XCDs; within an XCD consecutive
 // workgroups take the row tiles of one token tile, so a W tile comes from HBM once and is
@@ -26,7 +26,6 @@ namespace {
 
 constexpr int BM = 256, BN = 256, BK = 32;
 constexpr int kStageChunks = (BM + BN) * 4;  // 16-byte chunks per stage: A rows then B rows
-constexpr int kEpiStride = 68;               // floats per staged row (64 + pad)
 
 __device__ inline int swz4(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }
 
@@ -47,6 +46,18 @@ __device__ inline void wait_newer() {
   if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
   if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+}
+// max(x, x rotated right by N inside its row of 16 lanes) in one instruction.  The s_nop covers
+// the two wait states a DPP read needs after a vector write of its source.
+template <int N>
+__device__ inline float max_ror(float x) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "add the rotation");
+  float r;
+  if constexpr (N == 8) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  if constexpr (N == 4) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:4 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  if constexpr (N == 2) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:2 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  if constexpr (N == 1) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:1 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  return r;
 }
 __device__ inline uint32_t lds_offset(const void* p) {
   return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)p);
@@ -164,52 +175,97 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
     if (kt + 2 < nk) step(st2, st3, st1, kt + 2);
     if (kt + 3 < nk) step(st3, st0, st2, kt + 3);
   }
-  lds_barrier();  // everybody is done with the operand stages; st0..st2 become epilogue scratch
 
-  // Epilogue.  D layout of the 32x32 MFMA: lane holds D[8 (r/4) + 4 h + r%4][j32], r = 0..15.
-  // Each wavefront stages 32 rows x 64 tokens at a time in its own scratch region.
-  float* scratch = reinterpret_cast<float*>(wave < 3 ? st0 : wave < 6 ? st1 : st2) + (wave % 3) * (32 * kEpiStride);
-  const int c4 = (lane & 15) * 4, rsub = lane >> 4;
+  // Epilogue, straight from the accumulators.  D layout of the 32x32 MFMA: lane holds
+  // D[8 (r/4) + 4 h + r%4][j32], r = 0..15, so for a fixed r the 32 lanes of a half-wavefront hold
+  // 32 consecutive tokens of one row: a dword store writes two full 128-byte lines, and the
+  // (max, sum exp) over the wavefront's 64 tokens is a reduction over those 32 lanes (four DPP
+  // steps inside rows of 16 lanes and one swap of the two rows).  No LDS, and no branch in the
+  // interior tiles, so the 64 independent (row tile, r) chains interleave freely.
+  constexpr float kLog2e = 1.4426950408889634f;
+  const float sc = a.inv_tau;
+  const int mw = m0 + wm * 128;  // first row of this wavefront
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int jp = 0; jp < TJ / 2; ++jp) {
+    const int vbase = n0 + wn * (32 * TJ) + jp * 64;
+    const int ptile = vbase / kTiledTn;
+    const int v0 = vbase + j32, v1 = v0 + 32;
+    float* lbase = a.logits + (size_t)(mw + 4 * h) * a.ldl + v0;
+    float2* pbase = a.partials + (size_t)(mw + 4 * h) * a.nT + ptile;
+    if (mw + 128 <= M && vbase + 64 <= a.V) {  // interior: wavefront-uniform
 #pragma unroll
-    for (int jp = 0; jp < TJ / 2; ++jp) {
-      const int vbase = n0 + wn * (32 * TJ) + jp * 64;
-      const int ptile = vbase / kTiledTn;
+      for (int i = 0; i < 4; ++i) {
+        // phase by phase over the 16 accumulator indices, so that the 16 reduction chains are
+        // independent neighbours in program order
+        float mx[16], e[16];
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          scratch[(8 * (r >> 2) + 4 * h + (r & 3)) * kEpiStride + j * 32 + j32] = acc[i][jp * 2 + j][r] * a.inv_tau;
-      // the wavefront re-reads only its own region; LDS operations of one wavefront stay in order
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int rl = it * 4 + rsub;
-        const floatx4 v4 = *reinterpret_cast<const floatx4*>(scratch + rl * kEpiStride + c4);
-        const int m = m0 + wm * 128 + i * 32 + rl;
-        const int v = vbase + c4;
-        const bool row_ok = m < M;
-        float* dst = a.logits + (size_t)m * a.ldl + v;
-        float mx = -INFINITY;
-        if (row_ok && v + 3 < a.V) {
-          *reinterpret_cast<floatx4*>(dst) = v4;
-          mx = fmaxf(fmaxf(v4[0], v4[1]), fmaxf(v4[2], v4[3]));
-        } else if (row_ok) {
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            if (v + q < a.V) { dst[q] = v4[q]; mx = fmaxf(mx, v4[q]); }
+        for (int r = 0; r < 16; ++r) {
+          const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
+          const float l0 = acc[i][jp * 2][r] * sc, l1 = acc[i][jp * 2 + 1][r] * sc;
+          acc[i][jp * 2][r] = l0;
+          acc[i][jp * 2 + 1][r] = l1;
+          float* dst = lbase + (size_t)mr * a.ldl;
+          dst[0] = l0;
+          dst[32] = l1;
+          mx[r] = l0 > l1 ? l0 : l1;
         }
-        mx = row16_max(mx);
-        float e = 0.f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (row_ok && v + q < a.V) e += __expf(v4[q] - mx);
-        e = row16_sum(e);
-        if ((lane & 15) == 0 && row_ok && vbase < a.V)
-          a.partials[(size_t)m * a.nT + ptile] = make_float2(mx, e);
+        for (int r = 0; r < 16; ++r) mx[r] = max_ror<8>(mx[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx[r] = max_ror<4>(mx[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx[r] = max_ror<2>(mx[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx[r] = max_ror<1>(mx[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e[r] = swap16(mx[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx[r] = mx[r] > e[r] ? mx[r] : e[r];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float mb = mx[r] * kLog2e;
+          e[r] = __builtin_amdgcn_exp2f(fmaf(acc[i][jp * 2][r], kLog2e, -mb)) +
+                 __builtin_amdgcn_exp2f(fmaf(acc[i][jp * 2 + 1][r], kLog2e, -mb));
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e[r] += row_ror<8>(e[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e[r] += row_ror<4>(e[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e[r] += row_ror<2>(e[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e[r] += row_ror<1>(e[r]);
+        float t[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t[r] = swap16(e[r]);
+        // every lane of a half-wavefront holds its row's pair and writes it to the same address
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
+          pbase[(size_t)mr * a.nT] = make_float2(mx[r], e[r] + t[r]);
+        }
       }
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    } else if (vbase < a.V) {  // edge tiles: rows past M and tokens past V are masked
+      const bool ok0 = v0 < a.V, ok1 = v1 < a.V;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
+          const bool row_ok = mw + 4 * h + mr < M;
+          const float l0 = acc[i][jp * 2][r] * sc, l1 = acc[i][jp * 2 + 1][r] * sc;
+          float* dst = lbase + (size_t)mr * a.ldl;
+          if (row_ok && ok0) dst[0] = l0;
+          if (row_ok && ok1) dst[32] = l1;
+          float mx = row16_max(fmaxf(ok0 ? l0 : -INFINITY, ok1 ? l1 : -INFINITY));
+          mx = fmaxf(mx, swap16(mx));  // finite: token vbase itself is valid
+          const float mb = mx * kLog2e;
+          float e = (ok0 ? exp2f(fmaf(l0, kLog2e, -mb)) : 0.f) + (ok1 ? exp2f(fmaf(l1, kLog2e, -mb)) : 0.f);
+          e = row16_sum(e);
+          e += swap16(e);
+          if (j32 == 0 && row_ok) pbase[(size_t)mr * a.nT] = make_float2(mx, e);
+        }
+      }
     }
   }
 }
