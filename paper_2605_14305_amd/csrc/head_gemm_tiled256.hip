@@ -138,20 +138,53 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
   // for its own 4 loads of it; the 4 of stage kt+2 may stay in flight) and tells that everybody
   // has left stage kt-1, which is then refilled with k-step kt+3.  Because stage kt+1 is
   // already visible, its first k-slice is fetched under the last multiplies of stage kt.
+  //
+  // Steady-state form (kt + 3 < nk): no conditionals, so the step is one basic block, and the
+  // fragment reads sit in the middle of a run of multiplies: the compiler cannot see through
+  // the hand-written barrier and load statements and waits for every outstanding LDS read
+  // before the first multiply that follows them, so each batch of reads is issued when the
+  // previous batch has long returned and four multiplies ahead of its first use.
+  auto mfma_pair = [&](const Frag& f, int i) {
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+  };
+  auto step_steady = [&](const bf16x8* st_cur, const bf16x8* st_next, bf16x8* refill, int kt) {
+    __builtin_amdgcn_sched_barrier(0);  // the multiplies of the previous step stay in front of the barrier
+    wait_newer<2 * QI>();
+    lds_barrier();
+    mfma_pair(cur, 0);
+    issue_one(refill, kt + 3, 0);
+    mfma_pair(cur, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frag(st_cur, 1, nxt);
+    issue_one(refill, kt + 3, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_pair(cur, 2);
+    issue_one(refill, kt + 3, 2);
+    mfma_pair(cur, 3);
+    issue_one(refill, kt + 3, 3);
+#pragma unroll
+    for (int n = 4; n < 2 * QI; ++n) issue_one(refill, kt + 3, n);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_pair(nxt, 0);
+    mfma_pair(nxt, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frag(st_next, 0, cur);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_pair(nxt, 2);
+    mfma_pair(nxt, 3);
+  };
+  // General form for the last steps of the k loop (nothing left to refill, no next stage).
   auto step = [&](const bf16x8* st_cur, const bf16x8* st_next, bf16x8* refill, int kt) {
     if (kt + 2 < nk) wait_newer<2 * QI>();
     else wait_newer<0>();
     lds_barrier();
     read_frag(st_cur, 1, nxt);
-    // The refill loads are spread between the multiplies: a wavefront issues in order, and eight
-    // wavefronts pushing all their loads right after the barrier fill the address FIFO and stall
-    // in front of their own MFMAs.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (kt + 3 < nk && i < 2 * QI) issue_one(refill, kt + 3, i);
-#pragma unroll
-      for (int j = 0; j < TJ; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
+      mfma_pair(cur, i);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
@@ -169,7 +202,14 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
   else wait_newer<0>();
   lds_barrier();
   read_frag(st0, 0, cur);
-  for (int kt = 0; kt < nk; kt += 4) {
+  int kt = 0;
+  for (; kt + 6 < nk; kt += 4) {  // all four steps refill: kt + 3 + 3 < nk
+    step_steady(st0, st1, st3, kt);
+    step_steady(st1, st2, st0, kt + 1);
+    step_steady(st2, st3, st1, kt + 2);
+    step_steady(st3, st0, st2, kt + 3);
+  }
+  for (; kt < nk; kt += 4) {
     step(st0, st1, st3, kt);
     if (kt + 1 < nk) step(st1, st2, st0, kt + 1);
     if (kt + 2 < nk) step(st2, st3, st1, kt + 2);
