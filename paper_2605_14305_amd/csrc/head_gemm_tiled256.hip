@@ -73,7 +73,8 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
   // one array per stage, so the compiler can tell the in-flight LDS writes of the other stages
   // from the fragment reads of the current one
   __shared__ bf16x8 st0[kStageChunks], st1[kStageChunks], st2[kStageChunks], st3[kStageChunks];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: LDS offsets of the loads need no lane readback
   const int wm = wave / WN, wn = wave % WN;
   const int j32 = lane & 31, h = lane >> 5;
   const int M = a.nrows;
@@ -96,11 +97,20 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
     gp[q] = h_row(a, r) + c * 8;
     gp[QI + q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
   }
+  // gp[] point at k-step `kbase`; the steady-state loop advances them by one k-step per step
+  // (one 64-bit add per load) instead of forming base + offset each time.
+  int kbase = 0;
+  auto stage_slot = [&](bf16x8* stage, int n) {
+    return lds_offset(stage + (n < QI ? 0 : BM * 4) + (wave * (16 * QI) + (n % QI) * 16) * 4);
+  };
   // load n (0 .. 2 QI - 1) of this wavefront for k-step kt: A rows first, then B rows
   auto issue_one = [&](bf16x8* stage, int kt, int n) {
-    const int q = n % QI;
-    bf16x8* dst = stage + (n < QI ? 0 : BM * 4) + (wave * (16 * QI) + q * 16) * 4;
-    load_to_lds_16(gp[n] + kt * BK, lds_offset(dst));
+    load_to_lds_16(gp[n] + (kt - kbase) * BK, stage_slot(stage, n));
+  };
+  // the same for the k-step gp[n] points at, which then moves on by one
+  auto issue_next = [&](bf16x8* stage, int n) {
+    load_to_lds_16(gp[n], stage_slot(stage, n));
+    gp[n] += BK;
   };
   auto issue = [&](bf16x8* stage, int kt) {
 #pragma unroll
@@ -149,23 +159,23 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
     for (int j = 0; j < TJ; ++j)
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
   };
-  auto step_steady = [&](const bf16x8* st_cur, const bf16x8* st_next, bf16x8* refill, int kt) {
+  auto step_steady = [&](const bf16x8* st_cur, const bf16x8* st_next, bf16x8* refill) {
     __builtin_amdgcn_sched_barrier(0);  // the multiplies of the previous step stay in front of the barrier
     wait_newer<2 * QI>();
     lds_barrier();
     mfma_pair(cur, 0);
-    issue_one(refill, kt + 3, 0);
+    issue_next(refill, 0);
     mfma_pair(cur, 1);
     __builtin_amdgcn_sched_barrier(0);
     read_frag(st_cur, 1, nxt);
-    issue_one(refill, kt + 3, 1);
+    issue_next(refill, 1);
     __builtin_amdgcn_sched_barrier(0);
     mfma_pair(cur, 2);
-    issue_one(refill, kt + 3, 2);
+    issue_next(refill, 2);
     mfma_pair(cur, 3);
-    issue_one(refill, kt + 3, 3);
+    issue_next(refill, 3);
 #pragma unroll
-    for (int n = 4; n < 2 * QI; ++n) issue_one(refill, kt + 3, n);
+    for (int n = 4; n < 2 * QI; ++n) issue_next(refill, n);
     __builtin_amdgcn_sched_barrier(0);
     mfma_pair(nxt, 0);
     mfma_pair(nxt, 1);
@@ -203,11 +213,17 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
   lds_barrier();
   read_frag(st0, 0, cur);
   int kt = 0;
+  if (6 < nk) {  // the steady loop refills k-step kt + 3: point the loads there
+#pragma unroll
+    for (int n = 0; n < 2 * QI; ++n) gp[n] += 3 * BK;
+    kbase = 3;
+  }
   for (; kt + 6 < nk; kt += 4) {  // all four steps refill: kt + 3 + 3 < nk
-    step_steady(st0, st1, st3, kt);
-    step_steady(st1, st2, st0, kt + 1);
-    step_steady(st2, st3, st1, kt + 2);
-    step_steady(st3, st0, st2, kt + 3);
+    step_steady(st0, st1, st3);
+    step_steady(st1, st2, st0);
+    step_steady(st2, st3, st1);
+    step_steady(st3, st0, st2);
+    kbase += 4;
   }
   for (; kt < nk; kt += 4) {
     step(st0, st1, st3, kt);
