@@ -199,6 +199,7 @@ def main():
     roof.update({"kernel": {fb.FEF_GEMM_SKINNY: "head_skinny_kernel" if M <= 16 else "head_skinny32_kernel",
                             fb.FEF_GEMM_TILED: "head_tiled_kernel",
                             fb.FEF_GEMM_TILED256: "head_tiled256_kernel",
+                            fb.FEF_GEMM_STREAM128: "head_stream128_kernel",
                             fb.FEF_GEMM_F32: "head_f32_kernel"}[variant],
                  "avg_kernel_us": head_avg_s * 1e6, "algorithmic_bytes": hb, "flops": flops,
                  "events": "separate" if args.graph else args.events})

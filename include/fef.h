@@ -73,9 +73,11 @@ typedef enum {
 typedef enum {
   FEF_GEMM_AUTO = 0,
   FEF_GEMM_SKINNY = 1, /* bf16, M <= 32, d in {512, 3584, 4096}: W streamed once, split-k  */
-  FEF_GEMM_TILED = 2,  /* bf16, any M: 128x128 LDS-tiled MFMA GEMM (AUTO: M <= 128)        */
+  FEF_GEMM_TILED = 2,  /* bf16, any M: plain 128x128 LDS-tiled MFMA GEMM (never picked by AUTO) */
   FEF_GEMM_F32 = 3,    /* f32, any shape: reference-grade FMA kernel                       */
-  FEF_GEMM_TILED256 = 4 /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)        */
+  FEF_GEMM_TILED256 = 4, /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)       */
+  FEF_GEMM_STREAM128 = 5 /* bf16, M <= 128: all rows x 256 tokens per workgroup, W streamed
+                            through a six-stage LDS ring (AUTO: 32 < M <= 128)              */
 } fef_gemm_variant;
 
 /* In Algorithm 2 the verification inputs X^(j_m) carry the draft prefix, so a real target

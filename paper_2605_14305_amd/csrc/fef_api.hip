@@ -66,7 +66,7 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
   if (v == FEF_GEMM_AUTO) {
     if (p->dtype == FEF_F32) v = FEF_GEMM_F32;
     else if (fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d)) v = FEF_GEMM_SKINNY;
-    else v = M > 128 ? FEF_GEMM_TILED256 : FEF_GEMM_TILED;
+    else v = M > 128 ? FEF_GEMM_TILED256 : FEF_GEMM_STREAM128;
   }
   switch (v) {
     case FEF_GEMM_SKINNY:
@@ -76,6 +76,10 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
     case FEF_GEMM_TILED:
     case FEF_GEMM_TILED256:
       if (p->dtype != FEF_BF16) return fail(FEF_ERR_UNSUPPORTED, "tiled head kernels are bf16 only");
+      break;
+    case FEF_GEMM_STREAM128:
+      if (p->dtype != FEF_BF16 || !fef::stream128_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d))
+        return fail(FEF_ERR_UNSUPPORTED, "streaming head kernel needs bf16 and at most 128 rows through the head");
       break;
     case FEF_GEMM_F32:
       if (p->dtype != FEF_F32) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel needs dtype f32");
@@ -194,6 +198,7 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
     case FEF_GEMM_SKINNY: e = fef::launch_head_skinny(h); break;
     case FEF_GEMM_TILED: e = fef::launch_head_tiled(h); break;
     case FEF_GEMM_TILED256: e = fef::launch_head_tiled256(h); break;
+    case FEF_GEMM_STREAM128: e = fef::launch_head_stream128(h); break;
     default: e = fef::launch_head_f32(h); break;
   }
   if (e != hipSuccess) return fail(FEF_ERR_HIP, "head kernel launch: %s", hipGetErrorString(e));

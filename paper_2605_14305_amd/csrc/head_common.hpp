@@ -62,4 +62,138 @@ __device__ inline float row16_sum(float x) {
   return x;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Pieces shared by the LDS-tiled MFMA kernels (32-wide k-steps, v_mfma_f32_32x32x16_bf16).
+// ---------------------------------------------------------------------------------------------
+
+// LDS tiles of [rows][32 k] bf16 = 64 B per row = four 16-byte chunks.  The LDS has 64 four-byte
+// banks, i.e. four such rows per sweep, so chunk c of row r is kept at position c ^ ((r >> 2) & 3):
+// the 16-byte fragment reads of 16 consecutive rows then touch every bank once.
+__device__ inline int swz4(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }
+
+// global_load_lds_dwordx4: lane l copies 16 bytes from its global address to LDS offset
+// lds_off + 16 l (lds_off wavefront-uniform, carried in M0).  Written as inline assembly so
+// that the compiler's wait-count pass does not tie the fragment reads of one stage to the
+// loads still in flight for the others (it would drain them all once per ring cycle);
+// completion is tracked by hand with vmcnt before the workgroup barrier.
+__device__ inline void load_to_lds_16(const void* gptr, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(gptr), "s"(lds_off) : "memory");
+}
+// Wait until at most N of this wavefront's vector-memory operations are outstanding.
+template <int N>
+__device__ inline void wait_newer() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+__device__ inline uint32_t lds_offset(const void* p) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)p);
+}
+// max(x, x rotated right by N inside its row of 16 lanes) in one instruction.  The s_nop covers
+// the two wait states a DPP read needs after a vector write of its source.
+template <int N>
+__device__ inline float max_ror(float x) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "add the rotation");
+  float r;
+  if constexpr (N == 8) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  if constexpr (N == 4) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:4 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  if constexpr (N == 2) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:2 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  if constexpr (N == 1) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:1 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  return r;
+}
+
+// Epilogue of a wavefront that holds NI x 2 accumulator tiles of 32 x 32: rows mw .. mw + 32 NI - 1,
+// tokens vbase .. vbase + 63.  Writes the scaled logits and one (max, sum exp) partial per row.
+// D layout of the 32x32 MFMA: lane holds D[8 (r/4) + 4 h + r%4][j32], r = 0..15, so for a fixed r
+// the 32 lanes of a half-wavefront hold 32 consecutive tokens of one row: a dword store writes two
+// full 128-byte lines, and the (max, sum exp) over the 64 tokens is a reduction over those 32
+// lanes (four DPP steps inside rows of 16 lanes and one swap of the two rows).  No LDS, and no
+// branch in the interior tiles, so the 16 NI independent (row tile, r) chains interleave freely.
+template <int NI>
+__device__ inline void store_logits_and_partials(const HeadArgs& a, floatx16 (&acc)[NI][2], int mw, int vbase,
+                                                 int M, int lane) {
+  constexpr float kLog2e = 1.4426950408889634f;
+  const int j32 = lane & 31, h = lane >> 5;
+  const float sc = a.inv_tau;
+  const int ptile = vbase / kTiledTn;
+  const int v0 = vbase + j32, v1 = v0 + 32;
+  float* lbase = a.logits + (size_t)(mw + 4 * h) * a.ldl + v0;
+  float2* pbase = a.partials + (size_t)(mw + 4 * h) * a.nT + ptile;
+  if (mw + 32 * NI <= M && vbase + 64 <= a.V) {  // interior: wavefront-uniform
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      // phase by phase over the 16 accumulator indices, so that the 16 reduction chains are
+      // independent neighbours in program order
+      float mx[16], e[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
+        const float l0 = acc[i][0][r] * sc, l1 = acc[i][1][r] * sc;
+        acc[i][0][r] = l0;
+        acc[i][1][r] = l1;
+        float* dst = lbase + (size_t)mr * a.ldl;
+        dst[0] = l0;
+        dst[32] = l1;
+        mx[r] = l0 > l1 ? l0 : l1;
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = max_ror<8>(mx[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = max_ror<4>(mx[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = max_ror<2>(mx[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = max_ror<1>(mx[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e[r] = swap16(mx[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx[r] = mx[r] > e[r] ? mx[r] : e[r];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float mb = mx[r] * kLog2e;
+        e[r] = __builtin_amdgcn_exp2f(fmaf(acc[i][0][r], kLog2e, -mb)) +
+               __builtin_amdgcn_exp2f(fmaf(acc[i][1][r], kLog2e, -mb));
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e[r] += row_ror<8>(e[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e[r] += row_ror<4>(e[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e[r] += row_ror<2>(e[r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e[r] += row_ror<1>(e[r]);
+      float t[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t[r] = swap16(e[r]);
+      // every lane of a half-wavefront holds its row's pair and writes it to the same address
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
+        pbase[(size_t)mr * a.nT] = make_float2(mx[r], e[r] + t[r]);
+      }
+    }
+  } else if (vbase < a.V) {  // edge tiles: rows past M and tokens past V are masked
+    const bool ok0 = v0 < a.V, ok1 = v1 < a.V;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
+        const bool row_ok = mw + 4 * h + mr < M;
+        const float l0 = acc[i][0][r] * sc, l1 = acc[i][1][r] * sc;
+        float* dst = lbase + (size_t)mr * a.ldl;
+        if (row_ok && ok0) dst[0] = l0;
+        if (row_ok && ok1) dst[32] = l1;
+        float mx = row16_max(fmaxf(ok0 ? l0 : -INFINITY, ok1 ? l1 : -INFINITY));
+        mx = fmaxf(mx, swap16(mx));  // finite: token vbase itself is valid
+        const float mb = mx * kLog2e;
+        float e = (ok0 ? exp2f(fmaf(l0, kLog2e, -mb)) : 0.f) + (ok1 ? exp2f(fmaf(l1, kLog2e, -mb)) : 0.f);
+        e = row16_sum(e);
+        e += swap16(e);
+        if (j32 == 0 && row_ok) pbase[(size_t)mr * a.nT] = make_float2(mx, e);
+      }
+    }
+  }
+}
+
 }  // namespace fef

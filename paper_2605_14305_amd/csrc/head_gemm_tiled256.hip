@@ -27,44 +27,8 @@ namespace {
 constexpr int BM = 256, BN = 256, BK = 32;
 constexpr int kStageChunks = (BM + BN) * 4;  // 16-byte chunks per stage: A rows then B rows
 
-__device__ inline int swz4(int row, int chunk) { return row * 4 + (chunk ^ ((row >> 2) & 3)); }
-
-// global_load_lds_dwordx4: lane l copies 16 bytes from its global address to LDS offset
-// lds_off + 16 l (lds_off wavefront-uniform, carried in M0).  Written as inline assembly so
-// that the compiler's wait-count pass does not tie the fragment reads of one stage to the
-// loads still in flight for the others (it would drain them all once per ring cycle);
-// completion is tracked by hand with vmcnt before the workgroup barrier.
-__device__ inline void load_to_lds_16(const void* gptr, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(gptr), "s"(lds_off) : "memory");
-}
-// Wait until at most N of this wavefront's vector-memory operations are outstanding.
-template <int N>
-__device__ inline void wait_newer() {
-  static_assert(N == 0 || N == 4 || N == 8 || N == 16, "add the count");
-  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-}
-// max(x, x rotated right by N inside its row of 16 lanes) in one instruction.  The s_nop covers
-// the two wait states a DPP read needs after a vector write of its source.
-template <int N>
-__device__ inline float max_ror(float x) {
-  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "add the rotation");
-  float r;
-  if constexpr (N == 8) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
-  if constexpr (N == 4) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:4 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
-  if constexpr (N == 2) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:2 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
-  if constexpr (N == 1) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:1 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
-  return r;
-}
-__device__ inline uint32_t lds_offset(const void* p) {
-  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)p);
-}
-
-// TJ = 32-token tiles per wavefront: 2 -> eight wavefronts of 128 x 64 (used), 4 -> four of
-// 128 x 128 (one wavefront per SIMD; measured slower: 874 vs 920 TFLOP/s at M = 2048).
+// TJ = 32-token tiles per wavefront: 2 -> eight wavefronts of 128 x 64.  (4 -> four wavefronts of
+// 128 x 128, one per SIMD, was measured slower and is not instantiated.)
 template <int TJ>
 __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_kernel(HeadArgs a, int m_tiles, int n_tiles) {
   constexpr int WN = BN / (32 * TJ);      // wavefronts along the token dimension
@@ -232,98 +196,9 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
     if (kt + 3 < nk) step(st3, st0, st2, kt + 3);
   }
 
-  // Epilogue, straight from the accumulators.  D layout of the 32x32 MFMA: lane holds
-  // D[8 (r/4) + 4 h + r%4][j32], r = 0..15, so for a fixed r the 32 lanes of a half-wavefront hold
-  // 32 consecutive tokens of one row: a dword store writes two full 128-byte lines, and the
-  // (max, sum exp) over the wavefront's 64 tokens is a reduction over those 32 lanes (four DPP
-  // steps inside rows of 16 lanes and one swap of the two rows).  No LDS, and no branch in the
-  // interior tiles, so the 64 independent (row tile, r) chains interleave freely.
-  constexpr float kLog2e = 1.4426950408889634f;
-  const float sc = a.inv_tau;
-  const int mw = m0 + wm * 128;  // first row of this wavefront
-#pragma unroll
-  for (int jp = 0; jp < TJ / 2; ++jp) {
-    const int vbase = n0 + wn * (32 * TJ) + jp * 64;
-    const int ptile = vbase / kTiledTn;
-    const int v0 = vbase + j32, v1 = v0 + 32;
-    float* lbase = a.logits + (size_t)(mw + 4 * h) * a.ldl + v0;
-    float2* pbase = a.partials + (size_t)(mw + 4 * h) * a.nT + ptile;
-    if (mw + 128 <= M && vbase + 64 <= a.V) {  // interior: wavefront-uniform
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        // phase by phase over the 16 accumulator indices, so that the 16 reduction chains are
-        // independent neighbours in program order
-        float mx[16], e[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
-          const float l0 = acc[i][jp * 2][r] * sc, l1 = acc[i][jp * 2 + 1][r] * sc;
-          acc[i][jp * 2][r] = l0;
-          acc[i][jp * 2 + 1][r] = l1;
-          float* dst = lbase + (size_t)mr * a.ldl;
-          dst[0] = l0;
-          dst[32] = l1;
-          mx[r] = l0 > l1 ? l0 : l1;
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx[r] = max_ror<8>(mx[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx[r] = max_ror<4>(mx[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx[r] = max_ror<2>(mx[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx[r] = max_ror<1>(mx[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) e[r] = swap16(mx[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx[r] = mx[r] > e[r] ? mx[r] : e[r];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float mb = mx[r] * kLog2e;
-          e[r] = __builtin_amdgcn_exp2f(fmaf(acc[i][jp * 2][r], kLog2e, -mb)) +
-                 __builtin_amdgcn_exp2f(fmaf(acc[i][jp * 2 + 1][r], kLog2e, -mb));
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) e[r] += row_ror<8>(e[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) e[r] += row_ror<4>(e[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) e[r] += row_ror<2>(e[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) e[r] += row_ror<1>(e[r]);
-        float t[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t[r] = swap16(e[r]);
-        // every lane of a half-wavefront holds its row's pair and writes it to the same address
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
-          pbase[(size_t)mr * a.nT] = make_float2(mx[r], e[r] + t[r]);
-        }
-      }
-    } else if (vbase < a.V) {  // edge tiles: rows past M and tokens past V are masked
-      const bool ok0 = v0 < a.V, ok1 = v1 < a.V;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
-          const bool row_ok = mw + 4 * h + mr < M;
-          const float l0 = acc[i][jp * 2][r] * sc, l1 = acc[i][jp * 2 + 1][r] * sc;
-          float* dst = lbase + (size_t)mr * a.ldl;
-          if (row_ok && ok0) dst[0] = l0;
-          if (row_ok && ok1) dst[32] = l1;
-          float mx = row16_max(fmaxf(ok0 ? l0 : -INFINITY, ok1 ? l1 : -INFINITY));
-          mx = fmaxf(mx, swap16(mx));  // finite: token vbase itself is valid
-          const float mb = mx * kLog2e;
-          float e = (ok0 ? exp2f(fmaf(l0, kLog2e, -mb)) : 0.f) + (ok1 ? exp2f(fmaf(l1, kLog2e, -mb)) : 0.f);
-          e = row16_sum(e);
-          e += swap16(e);
-          if (j32 == 0 && row_ok) pbase[(size_t)mr * a.nT] = make_float2(mx, e);
-        }
-      }
-    }
-  }
+  // Epilogue: logits and per-row (max, sum exp) partials straight from the accumulators.
+  static_assert(TJ == 2, "the epilogue covers 64 tokens per wavefront");
+  store_logits_and_partials<4>(a, acc, m0 + wm * 128, n0 + wn * 64, M, lane);
 }
 
 }  // namespace

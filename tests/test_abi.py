@@ -55,10 +55,12 @@ def test_gemm_selection(lib):
     assert fb.fef_select_gemm(fb.make_params(1, 3584, 151936), 8) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(1, 4096, 126464), 16) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(2, 4096, 126464), 8) == fb.FEF_GEMM_SKINNY
-    assert fb.fef_select_gemm(fb.make_params(3, 4096, 126464), 8) == fb.FEF_GEMM_TILED
+    assert fb.fef_select_gemm(fb.make_params(3, 4096, 126464), 8) == fb.FEF_GEMM_STREAM128
     assert fb.fef_select_gemm(fb.make_params(16, 4096, 126464), 8) == fb.FEF_GEMM_TILED256
-    assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_TILED
-    assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_TILED
+    assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_STREAM128
+    assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_STREAM128
+    p = fb.make_params(9, 4096, 126464, gemm_variant=fb.FEF_GEMM_STREAM128)
+    assert fb.fef_select_gemm(p, 8) == fb.FEF_ERR_UNSUPPORTED
     assert fb.fef_select_gemm(fb.make_params(1, 64, 32, dtype=fb.FEF_F32), 4) == fb.FEF_GEMM_F32
     p = fb.make_params(16, 4096, 126464, gemm_variant=fb.FEF_GEMM_SKINNY)
     assert fb.fef_select_gemm(p, 8) == fb.FEF_ERR_UNSUPPORTED
@@ -96,7 +98,7 @@ def test_argument_validation_happens_on_the_host(lib):
     p = good(); p.lowconf_scope = 2; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
     p = good(); p.lowconf_scope = 1; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))      # needs conf
     p = good(); p.pass_mask = 0x2000; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))     # needs conf
-    p = good(); p.gemm_variant = 9; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
+    p = good(); p.gemm_variant = 19; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
     p = good(); p.gemm_variant = fb.FEF_GEMM_TILED; cases.append((p, {}, fb.FEF_ERR_UNSUPPORTED))
     p = good(); cases.append((p, {"h": 0}, fb.FEF_ERR_INVALID_ARG))
     p = good(); cases.append((p, {"w": 0}, fb.FEF_ERR_INVALID_ARG))

@@ -135,6 +135,33 @@ def test_tiled256_kernel_small_shapes(B, K, d, V):
     assert st["near_flipped"] <= B // 20
 
 
+@pytest.mark.parametrize("B,K,d,V", [(5, 8, 64, 1000), (3, 5, 128, 777), (8, 8, 512, 2050), (1, 1, 64, 1),
+                                     (4, 16, 256, 300), (2, 9, 3584, 1500), (6, 8, 1024, 513)])
+def test_stream128_kernel_small_shapes(B, K, d, V):
+    """All rows x 256 tokens per workgroup, k halves added through LDS: 2 to 128 rows through the
+    head, k loops of 2 to 112 steps (prologue only, tail only, steady groups plus tail), ragged V."""
+    ref, out, st = run_case(B, K, max(K, 16), d, V, seed=16, rho=0.8, variant=fb.FEF_GEMM_STREAM128)
+    assert st["near_flipped"] <= B // 20
+
+
+def test_llada_shape_batch8_through_the_streaming_kernel(llada_head):
+    """B=8 at full d and V (128 rows through the head): the configuration AUTO gives the streaming
+    kernel; the oracle checks a seeded subset of sequences."""
+    wl, W, Wd, W64 = llada_head
+    B, K, block = 8, 8, 32
+    vs = fb.VerifyStep(B, K, block, wl.d, wl.V, device=DEV, diag=True)
+    assert fb.fef_select_gemm(vs._params(), K) == fb.FEF_GEMM_STREAM128
+    hd, ht = synth.make_hidden(B, K, wl.d, 9, wl.rho, wl.sigma_h, "bf16", 0, 2)
+    tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 9, step=2)
+    torch.cuda.synchronize()
+    for b in [0, 3, 7]:
+        r = O.verify_step(synth.to_f64(hd[b:b + 1]), synth.to_f64(ht[b:b + 1]), W64, K, block, 9, step=2,
+                          seq_base=b)
+        diag = {k: _np(v)[b:b + 1] if k != "lse" else _np(v)[:, b:b + 1] for k, v in vs.diag.items()}
+        st = parity.compare(r, _np(tok)[b:b + 1], _np(acc)[b:b + 1], _np(rem)[b:b + 1], diag)
+        print(f"seq {b}: {st}", flush=True)
+
+
 def test_very_large_vocabulary_generic_partial_merge():
     # more than 2560 partial tiles and 1024 residual chunks per row: the memory-resident code paths
     ref, out, st = run_case(2, 2, 16, 64, 270001, seed=14, rho=0.8, variant=fb.FEF_GEMM_TILED, with_logits=False)
@@ -154,7 +181,7 @@ def test_skinny_and_tiled_agree():
 def test_deterministic_bits():
     W = synth.make_head(5000, 512, 1).to(DEV)
     hd, ht = (t.to(DEV) for t in synth.make_hidden(2, 4, 512, 1, 0.8, 3.0 / (0.02 * np.sqrt(512))))
-    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED, fb.FEF_GEMM_TILED256):
+    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED, fb.FEF_GEMM_TILED256, fb.FEF_GEMM_STREAM128):
         outs = []
         for rep in range(3):
             vs = fb.VerifyStep(2, 4, 8, 512, 5000, diag=True, diag_logits=True, gemm_variant=variant)
