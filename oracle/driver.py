@@ -46,7 +46,8 @@ class DecodeResult:
 
 
 def decode_block(hidden, W, B, K, block, seed, n_pass, n_rm=-1, temperature=1.0, seq_base=0,
-                 pos_base=0, step_base=0, lowconf_scope=0, max_rounds=None, recorrupt_prob=1.0):
+                 pos_base=0, step_base=0, lowconf_scope=0, max_rounds=None, recorrupt_prob=1.0,
+                 greedy=False):
     W = np.asarray(W, dtype=np.float64)
     X = np.full((B, block), MASK, np.int64)
     conf_out = np.zeros((B, block))
@@ -71,7 +72,8 @@ def decode_block(hidden, W, B, K, block, seed, n_pass, n_rm=-1, temperature=1.0,
                 res = O.verify_step(hd[b:b + 1], ht[b:b + 1], W, K, block, seed, temperature=temperature,
                                     step=step_base + r, seq_base=seq_base + b, pos_base=pos_base, n_rm=n_rm,
                                     final_pass=(s == n_pass - 1), lowconf_scope=lowconf_scope,
-                                    mask_in=mask, pass_mask=pmask, conf=conf, recorrupt_prob=recorrupt_prob)
+                                    mask_in=mask, pass_mask=pmask, conf=conf, recorrupt_prob=recorrupt_prob,
+                                    greedy=greedy)
                 C = int(res.committed[0])
                 for m in range(C):
                     X[b, res.slot_pos[0, m]] = res.tokens[0, m]
@@ -81,7 +83,8 @@ def decode_block(hidden, W, B, K, block, seed, n_pass, n_rm=-1, temperature=1.0,
                 marg = min(res.accept_margin[0, :last + 1].min() / 10.0,   # accept tolerance is 10x the CDF one
                            res.draft_gap[0, :last + 1].min(),
                            res.resid_gap[0] if a < w else np.inf,
-                           res.lowconf_gap[0])
+                           res.lowconf_gap[0],
+                           np.inf if res.argmax_gap is None else res.argmax_gap[:, 0, :last + 1].min() / 100.0)
                 min_margin[b] = min(min_margin[b], marg)
                 alphas.extend(res.alpha[0, :last + 1].tolist())
                 resolved = int(mask.sum()) - C == 0

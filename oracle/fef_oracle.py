@@ -6,8 +6,7 @@ call this.  It shares no code with the HIP path.  Every function is pinned by th
 suite against identities the paper proves (one-step identity in the proof of Theorem 1, the
 residual-distribution equation, Theorem 2), library routines, brute force on tiny inputs and
 the published Philox known-answer vectors.  Not pinned ("parity unpinned"): nothing that is
-implemented here; classifier-free guidance and greedy (temperature 0) verification are not
-implemented at all.
+implemented here; classifier-free guidance is not implemented at all.
 
 Notation follows the paper: rho / q = draft law, pi / p = target law, k = window, x~ = draft
 token, C = committed positions, alpha = sum_v min(p_v, q_v).
@@ -31,6 +30,13 @@ sequences; all sequences are vectorised with numpy, the window is an explicit lo
       R = LowConf_{n_rm}(C^(s)) and every selected position is re-corrupted through the
       absorbing forward kernel q(X_t^i | X_0^i): MASK with probability recorrupt_prob
       (= 1 - alpha-bar_t of that kernel; 1 by default), otherwise it keeps its token.
+
+  Greedy variant (greedy=True): the limit of S2-S5 as the sampling temperature goes to zero with
+  the logits fixed.  Both laws become point masses at their arg max (lowest token id on a tie),
+  so x~ = arg max of the draft logits, the ratio pi(x~)/rho(x~) is 1 when the two arg maxes agree
+  and 0 otherwise (u > 0 always rejects), and the residual law is the target's point mass:
+  Z = arg max of the target logits.  No uniform is drawn.  Confidences stay pi_tau(token) with
+  the finite temperature given, the quantity LowConf ranks.
 
 Readings of points the paper leaves open are listed with each function.
 """
@@ -61,6 +67,7 @@ class StepResult:
     draft_gap: np.ndarray       # [B,K] distance of the draft uniform to the nearest CDF edge
     resid_gap: np.ndarray       # [B]   same for the residual draw, relative to the residual mass
     lowconf_gap: np.ndarray     # [B]   confidence gap at the LowConf selection boundary
+    argmax_gap: np.ndarray = None  # [2,B,K] greedy only: top-1 minus top-2 scaled logit (draft, target)
     resid_fallbacks: int = 0    # times a rejection met a non-positive residual mass
     logits: np.ndarray = field(default=None, repr=False)  # [2,B,K,V] if requested
 
@@ -170,7 +177,7 @@ def recorrupt(selected, prob, seed, pos_base, step, sequence):
 def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0,
                 seq_base=0, pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0,
                 mask_in=None, pass_mask=None, conf=None, draft_tokens=None,
-                return_logits=False, recorrupt_prob=1.0):
+                return_logits=False, recorrupt_prob=1.0, greedy=False):
     """One speculative round for B sequences.
 
     h_draft, h_target: [B,K,d] float64 (row m belongs to window slot m); W: [V,d] float64.
@@ -191,6 +198,8 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
         the literal C^(s)) or over every position of the resolved block (scope 1).
       * a rejection that meets residual mass <= 0 (cannot happen in exact arithmetic)
         commits argmax p and is counted in resid_fallbacks.
+      * greedy=True: the zero-temperature limit described in the module header; `temperature`
+        then only scales the logits the confidences are taken from.
     """
     h_draft = np.asarray(h_draft, dtype=np.float64)
     h_target = np.asarray(h_target, dtype=np.float64)
@@ -220,6 +229,7 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
     resid_gap_slot = np.full((B, K), np.inf)
     fallbacks = np.zeros((B, K), bool)
     logits = np.zeros((2, B, K, V)) if return_logits else None
+    argmax_gap = np.full((2, B, K), np.inf) if greedy else None
 
     for m in range(K):
         active = m < window
@@ -234,8 +244,15 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
         alpha[:, m] = np.sum(np.minimum(p, q), axis=-1)
         r, resid_mass[:, m] = residual_law(p, q)
 
+        if greedy and V > 1:
+            for side, L in enumerate((Lq, Lp)):
+                top2 = np.partition(L, V - 2, axis=-1)[:, V - 2:]
+                argmax_gap[side, :, m] = top2[:, 1] - top2[:, 0]
+
         # S3: draft token
-        if draft_tokens is None:
+        if draft_tokens is None and greedy:
+            x = np.argmax(Lq, axis=-1)            # point mass of the draft law; first index on a tie
+        elif draft_tokens is None:
             u0 = philox.uniform(seed, abs_pos[:, m], step, seq, philox.STREAM_DRAFT)
             x, draft_gap[:, m] = inverse_cdf(q, u0)
         else:
@@ -252,6 +269,9 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
         accept[:, m] = u1 <= ratio
         accept_margin[:, m] = np.abs(u1 - ratio)
         p_tok[:, m], q_tok[:, m] = p[rows, x], q[rows, x]
+        if greedy:                                  # ratio of the two point masses: 1 or 0
+            accept[:, m] = x == np.argmax(Lp, axis=-1)
+            accept_margin[:, m] = np.inf
 
         # residual sample for this slot (used only where slot m is the first rejection)
         u2 = philox.uniform(seed, abs_pos[:, m], step, seq, philox.STREAM_RESIDUAL)
@@ -259,6 +279,11 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
         degenerate = resid_mass[:, m] <= 0.0
         z = np.where(degenerate, np.argmax(p, axis=-1), z)
         fallbacks[:, m] = degenerate
+        if greedy:                                  # residual of two point masses = the target's
+            z = np.argmax(Lp, axis=-1)
+            g = np.full(B, np.inf)
+            fallbacks[:, m] = False
+            degenerate = np.zeros(B, bool)
         resid_tok[:, m] = z
         resid_conf[:, m] = p[rows, z]
         with np.errstate(divide="ignore", invalid="ignore"):
@@ -307,7 +332,8 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
                       slot_pos=slot_pos, draft_tokens=x_draft.astype(np.int32), alpha=alpha,
                       resid_mass=resid_mass, lse=lse, p_draft_tok=p_tok, q_draft_tok=q_tok,
                       accept_margin=accept_margin, draft_gap=draft_gap, resid_gap=resid_gap,
-                      lowconf_gap=lowconf_gap, resid_fallbacks=n_fallback, logits=logits)
+                      lowconf_gap=lowconf_gap, resid_fallbacks=n_fallback, logits=logits,
+                      argmax_gap=argmax_gap)
 
 
 def expected_committed(alphas):
