@@ -25,6 +25,7 @@
  * stream 0 = draft sample, 1 = accept test, 2 = residual sample, 3 = re-corruption of a
  * selected position (masked iff u < recorrupt_prob); a word w becomes
  * u = ((w >> 9) + 0.5) * 2^-23.  A call is therefore a pure function of its arguments.
+ * (The greedy variant, fef_params.greedy, replaces the three token draws by arg maxes.)
  *
  * Conventions
  *   - Plain C.  Every data pointer below is a DEVICE pointer owned by the caller unless it
@@ -53,7 +54,7 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 3
+#define FEF_ABI_VERSION 4
 
 typedef enum {
   FEF_OK = 0,
@@ -143,6 +144,12 @@ typedef struct {
                                   seq_pass, a selection that re-corrupts nothing leaves no
                                   unresolved position for any later pass: the sequence is
                                   marked done (s = n_pass)                                     */
+  int32_t greedy;              /* 1: zero-temperature limit of the two laws.  Both become point
+                                  masses at their arg max (lowest token id on a tie): x~ = arg max
+                                  of the draft logits (or the given draft token), a slot is
+                                  accepted iff x~ equals the arg max of the target logits, the
+                                  corrected token is that arg max, and no uniform is drawn.
+                                  Confidences stay softmax(logits / tau)(token).  0: sample      */
 } fef_params;
 
 /* Bytes of device workspace a call with these sizes needs (depends on B, d, V, dtype,

@@ -43,7 +43,7 @@ class fef_params(ctypes.Structure):
         ("ev_head_begin", ctypes.c_void_p), ("ev_head_end", ctypes.c_void_p),
         ("n_pass", ctypes.c_int32), ("seq_pass", ctypes.c_void_p), ("seq_rounds", ctypes.c_void_p),
         ("tokens_state", ctypes.c_void_p), ("phase", ctypes.c_int32),
-        ("recorrupt_prob", ctypes.c_float),
+        ("recorrupt_prob", ctypes.c_float), ("greedy", ctypes.c_int32),
     ]
 
 
@@ -191,7 +191,7 @@ class VerifyStep:
     def __call__(self, h_draft, h_target, W_vocab, seed, *, temperature=1.0, step=0, seq_base=0,
                  pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0, mask_in=None, pass_mask=None,
                  conf=None, draft_tokens=None, head_events=None, n_pass=0, seq_pass=None, seq_rounds=None,
-                 tokens_state=None, phase=FEF_PHASE_FUSED, recorrupt_prob=1.0):
+                 tokens_state=None, phase=FEF_PHASE_FUSED, recorrupt_prob=1.0, greedy=False):
         for t, shape in ((h_draft, (self.B, self.K, self.d)), (h_target, (self.B, self.K, self.d)),
                          (W_vocab, (self.V, self.d))):
             if t is None:
@@ -214,6 +214,7 @@ class VerifyStep:
         p.draft_tokens = None if draft_tokens is None else draft_tokens.data_ptr()
         p.phase = phase
         p.recorrupt_prob = recorrupt_prob
+        p.greedy = int(greedy)
         p.n_pass = n_pass
         p.seq_pass = None if seq_pass is None else seq_pass.data_ptr()
         p.seq_rounds = None if seq_rounds is None else seq_rounds.data_ptr()
@@ -234,9 +235,9 @@ class BlockDecoder:
     speculative round on top of that state and reads nothing back, so the rounds of a block can
     be queued back to back; a sequence that has finished its last pass is left untouched."""
 
-    def __init__(self, step, n_pass, n_rm=-1, lowconf_scope=0, recorrupt_prob=1.0):
+    def __init__(self, step, n_pass, n_rm=-1, lowconf_scope=0, recorrupt_prob=1.0, greedy=False):
         self.vs, self.n_pass, self.n_rm, self.lowconf_scope = step, n_pass, n_rm, lowconf_scope
-        self.recorrupt_prob = recorrupt_prob
+        self.recorrupt_prob, self.greedy = recorrupt_prob, greedy
         B, block, dev = step.B, step.block, step.device
         self.mask = torch.ones(B, block, dtype=torch.uint8, device=dev)
         self.pass_mask = torch.zeros(B, block, dtype=torch.uint8, device=dev)
@@ -251,7 +252,7 @@ class BlockDecoder:
 
     def round(self, h_draft, h_target, W_vocab, seed, step, **kw):
         self.vs(h_draft, h_target, W_vocab, seed, step=step, n_rm=self.n_rm, lowconf_scope=self.lowconf_scope,
-                recorrupt_prob=self.recorrupt_prob,
+                recorrupt_prob=self.recorrupt_prob, greedy=self.greedy,
                 mask_in=self.mask, pass_mask=self.pass_mask, conf=self.conf, n_pass=self.n_pass,
                 seq_pass=self.seq_pass, seq_rounds=self.seq_rounds, tokens_state=self.tokens, **kw)
         # out_remask of this round is the mask of the next one (device-to-device, stream ordered)

@@ -24,7 +24,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Layout {
   int variant, nT, tile_unit, tile_T, nRC, all_slots;
   long ldl;
-  size_t off_logits, off_partials, off_lse, off_xdraft, off_slot_pos, off_window, off_seqstate,
+  size_t off_logits, off_partials, off_lse, off_xdraft, off_xtarget, off_slot_pos, off_window, off_seqstate,
       off_rmass, off_amass, total;
 };
 
@@ -49,6 +49,7 @@ fef_status check_sizes(const fef_params* p, int32_t K, int32_t block) {
     return fail(FEF_ERR_INVALID_ARG, "B*K = %ld exceeds 2^24 rows per call", (long)p->B * K);
   if (p->lowconf_scope != 0 && p->lowconf_scope != 1)
     return fail(FEF_ERR_INVALID_ARG, "lowconf_scope must be 0 or 1");
+  if (p->greedy != 0 && p->greedy != 1) return fail(FEF_ERR_INVALID_ARG, "greedy must be 0 or 1");
   if (!(p->recorrupt_prob > 0.f && p->recorrupt_prob <= 1.f))
     return fail(FEF_ERR_INVALID_ARG, "recorrupt_prob must lie in (0, 1]");
   if (p->phase != FEF_PHASE_FUSED && p->phase != FEF_PHASE_DRAFT && p->phase != FEF_PHASE_TARGET)
@@ -117,6 +118,7 @@ fef_status make_layout(const fef_params* p, int32_t K, int32_t block, Layout* L)
   L->off_partials = take(M * (size_t)L->nT * sizeof(float2));
   L->off_lse = take(M * sizeof(float));
   L->off_xdraft = take(BK * sizeof(int32_t));
+  L->off_xtarget = take(BK * sizeof(int32_t));
   L->off_slot_pos = take(BK * sizeof(int32_t));
   L->off_window = take((size_t)p->B * sizeof(int32_t));
   L->off_seqstate = take((size_t)p->B * sizeof(fef::SeqState));
@@ -212,12 +214,14 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   v.seed = seed; v.step = prm->step; v.seq_base = prm->seq_base; v.pos_base = prm->pos_base;
   v.n_rm = prm->n_rm; v.final_pass = prm->final_pass; v.lowconf_scope = prm->lowconf_scope;
   v.recorrupt_prob = prm->recorrupt_prob;
+  v.greedy = prm->greedy;
   v.mask_in = prm->mask_in; v.pass_mask = prm->pass_mask; v.conf = prm->conf;
   v.draft_tokens_in = prm->draft_tokens;
   v.n_pass = prm->n_pass; v.seq_pass = prm->seq_pass; v.seq_rounds = prm->seq_rounds;
   v.tokens_state = prm->tokens_state;
   v.lse = (float*)(ws + L.off_lse);
   v.xdraft = (int32_t*)(ws + L.off_xdraft);
+  v.xtarget = (int32_t*)(ws + L.off_xtarget);
   v.slot_pos = (int32_t*)(ws + L.off_slot_pos);
   v.window = (int32_t*)(ws + L.off_window);
   v.seqstate = (fef::SeqState*)(ws + L.off_seqstate);

@@ -98,6 +98,7 @@ struct VerifyArgs {
   uint32_t step, seq_base, pos_base;
   int n_rm, final_pass, lowconf_scope;
   float recorrupt_prob;
+  int greedy;
   const uint8_t* mask_in;
   uint8_t* pass_mask;
   float* conf;
@@ -109,6 +110,7 @@ struct VerifyArgs {
   // workspace
   float* lse;               // [2*B*K]
   int32_t* xdraft;          // [B*K]
+  int32_t* xtarget;         // [B*K] greedy variant: arg max of the target rows
   int32_t* slot_pos;        // [B*K]
   int32_t* window;          // [B]
   struct SeqState* seqstate;  // [B] accept-phase results handed to the final kernel

@@ -237,6 +237,26 @@ __device__ inline int window_slot(const VerifyArgs& a, int b, int m, int& unreso
   return wave_max_int(pos);
 }
 
+// Greedy variant: arg max of a logits row (lowest token id on a tie) from the head kernel's
+// partials.  Every partial maximum is the exact maximum of the stored logits of its tile, so the
+// first tile whose maximum equals the row maximum holds the answer, and the first token of that
+// tile whose stored logit equals it is the arg max.  Whole wavefront.
+__device__ inline int row_argmax(const VerifyArgs& a, const float2* P, const float* L, float row_max) {
+  const int lane = threadIdx.x & 63;
+  int cand = INT_MAX;
+  for (int t = lane; t < a.nT && cand == INT_MAX; t += kWave)
+    if (P[t].x == row_max) cand = t;
+  const int tile = wave_min_int(cand);
+  if (tile == INT_MAX) return 0;  // only if the row holds NaN
+  const int v0 = tile_start(a, tile);
+  const int nv = min(tile_start(a, tile + 1), a.V) - v0;
+  cand = INT_MAX;
+  for (int i = lane; i < nv && cand == INT_MAX; i += kWave)
+    if (L[v0 + i] == row_max) cand = i;
+  const int idx = wave_min_int(cand);
+  return idx == INT_MAX ? v0 : v0 + idx;
+}
+
 constexpr int kChunkPer = 16;  // residual chunks per lane in the one-wavefront final phase
 constexpr int kTilePer = 8;  // tokens per lane inside one partial tile: tiles of up to 512 tokens
 
@@ -288,7 +308,13 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
     a.lse[r] = lse;
     if (a.diag_lse) a.diag_lse[r] = lse;
   }
-  if (!is_draft) return;
+  if (!is_draft) {
+    if (a.greedy) {  // point mass of the target law
+      const int xt = row_argmax(a, P, a.logits + (size_t)r * a.ldl, mx);
+      if (lane == 0) a.xtarget[s] = xt;
+    }
+    return;
+  }
 
   int unresolved;
   const int pos = window_slot(a, b, m, unresolved);
@@ -301,6 +327,8 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
   if (m < window) {
     if (a.draft_tokens_in) {
       x = min(max(a.draft_tokens_in[s], 0), a.V - 1);  // keep the gathers in bounds
+    } else if (a.greedy) {
+      x = row_argmax(a, P, a.logits + (size_t)r * a.ldl, mx);  // point mass of the draft law
     } else {
       // x~ = min{v : sum_{w<=v} rho_w >= u}: first over vocabulary tiles, then inside the tile
       const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)pos, a.step,
@@ -381,7 +409,9 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
     const float* rm = a.rmass + (size_t)(a.all_slots ? s : b) * a.nRC;
     const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
                                    a.seq_base + (uint32_t)b, kStreamResidual);
-    if (a.nRC <= kWave * kChunkPer) {
+    if (a.greedy) {
+      z = a.xtarget[s];  // residual of two point masses: the target's
+    } else if (a.nRC <= kWave * kChunkPer) {
       // one wavefront, everything in registers
       if (tid < kWave) {
         float rmv[kChunkPer];
@@ -564,7 +594,8 @@ __global__ __launch_bounds__(NT) void accept_resid_kernel(VerifyArgs a) {
       const float ratio = fminf(1.f, expf(lp - lq));
       const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
                                      a.seq_base + (uint32_t)b, kStreamAccept);
-      rejected = !(u <= ratio);
+      // greedy: the ratio of the two point masses is 1 if the arg maxes agree, else 0
+      rejected = a.greedy ? x != a.xtarget[s] : !(u <= ratio);
       st.x[lane] = x;
       st.ptok[lane] = expf(lp);
     }
@@ -580,7 +611,9 @@ __global__ __launch_bounds__(NT) void accept_resid_kernel(VerifyArgs a) {
   const int acc_len = st.acc_len;
   const int m = a.all_slots ? y % a.K : acc_len;
   const int c = cg * NW + wave;
-  if (m < window && c < a.nRC) {  // otherwise nothing was rejected / slot beyond the window
+  // chunk masses: not needed when nothing was rejected, for slots beyond the window, or in the
+  // greedy variant (the corrected token is the target arg max) unless diagnostics want them
+  if (m < window && c < a.nRC && (!a.greedy || a.all_slots)) {
     const int s = b * a.K + m;
     const float* Lq = a.logits + (size_t)s * a.ldl;
     const float* Lp = a.logits + (size_t)(BK + s) * a.ldl;

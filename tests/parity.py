@@ -23,6 +23,7 @@ TOL_ACCEPT = 1e-4
 TOL_CDF = 1e-5
 TOL_CONF = 1e-5
 TOL_MASS = 1e-5
+TOL_ARGMAX = 1e-3     # greedy variant: top-1 minus top-2 scaled logit (5 x the logit tolerance)
 
 
 def compare(ref, tokens, accept_len, remask, diag=None, drafts_given=False, logit_atol=2e-4):
@@ -42,6 +43,8 @@ def compare(ref, tokens, accept_len, remask, diag=None, drafts_given=False, logi
                 near = True
         if a < w and ref.resid_gap[b] < TOL_CDF:
             near = True
+        if ref.argmax_gap is not None and w > 0 and ref.argmax_gap[:, b, :last + 1].min() < TOL_ARGMAX:
+            near = True
         near_remask = ref.lowconf_gap[b] < TOL_CONF
         same = int(accept_len[b]) == a and np.array_equal(tokens[b], ref.tokens[b])
         same_remask = np.array_equal(remask[b], ref.remask[b])
@@ -59,6 +62,8 @@ def compare(ref, tokens, accept_len, remask, diag=None, drafts_given=False, logi
         active = np.arange(K)[None, :] < ref.window[:, None]
         if "draft_tokens" in diag and not drafts_given:
             ok = active & (ref.draft_gap >= TOL_CDF)
+            if ref.argmax_gap is not None:
+                ok &= ref.argmax_gap[0] >= TOL_ARGMAX
             stats["draft_slots"] = int(active.sum())
             stats["draft_near"] = int((active & ~ok).sum())
             assert np.array_equal(diag["draft_tokens"][ok], ref.draft_tokens[ok])

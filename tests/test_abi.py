@@ -29,7 +29,7 @@ def test_exports_every_declared_symbol(lib):
     assert declared == set(fb.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.fef_abi_version() == 3
+    assert lib.fef_abi_version() == 4
 
 
 def test_struct_layout_matches(lib):
@@ -108,6 +108,7 @@ def test_argument_validation_happens_on_the_host(lib):
     p = good(); p.phase = 5; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
     p = good(); p.phase = fb.FEF_PHASE_TARGET; cases.append((p, {"out": 0}, fb.FEF_ERR_INVALID_ARG))
     p = good(); p.seq_pass = 0x4000; p.n_pass = 0; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
+    p = good(); p.greedy = 2; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
     for bad in (0.0, -0.5, 1.5, float("nan")):
         p = good(); p.recorrupt_prob = bad; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
     p = good(); p.workspace = 0; cases.append((p, {}, fb.FEF_ERR_WORKSPACE))

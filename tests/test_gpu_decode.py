@@ -15,11 +15,12 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-def _run(B, K, block, d, V, n_pass, n_rm, seed, rho=0.85, variant=fb.FEF_GEMM_AUTO, scope=0, recorrupt_prob=1.0):
+def _run(B, K, block, d, V, n_pass, n_rm, seed, rho=0.85, variant=fb.FEF_GEMM_AUTO, scope=0, recorrupt_prob=1.0,
+         greedy=False):
     W = synth.make_head(V, d, seed)
     sigma = 3.0 / (0.02 * np.sqrt(d))
     vs = fb.VerifyStep(B, K, block, d, V, device=DEV, gemm_variant=variant)
-    dec = fb.BlockDecoder(vs, n_pass, n_rm, scope, recorrupt_prob)
+    dec = fb.BlockDecoder(vs, n_pass, n_rm, scope, recorrupt_prob, greedy)
     R = dec.max_rounds()
     rounds = [synth.make_hidden(B, K, d, seed, rho, sigma, "bf16", 3, r) for r in range(R)]
     Wd = W.to(DEV)
@@ -35,7 +36,8 @@ def _run(B, K, block, d, V, n_pass, n_rm, seed, rho=0.85, variant=fb.FEF_GEMM_AU
             f64[r] = (synth.to_f64(rounds[r][0]), synth.to_f64(rounds[r][1]))
         return f64[r]
     ref = D.decode_block(hidden, synth.to_f64(W), B, K, block, seed, n_pass, n_rm, seq_base=20, pos_base=96,
-                         step_base=100, lowconf_scope=scope, max_rounds=R, recorrupt_prob=recorrupt_prob)
+                         step_base=100, lowconf_scope=scope, max_rounds=R, recorrupt_prob=recorrupt_prob,
+                         greedy=greedy)
     return dec, ref
 
 
@@ -81,6 +83,24 @@ def test_block_decode_with_stochastic_recorruption(prob):
     print(f"prob={prob}: {equal}/{B} identical, re-resolved positions per sequence {redo}", flush=True)
     assert equal >= B - 1
     assert min(redo) < 3 * (n_pass - 1)                    # some selection was only partly re-corrupted
+
+
+def test_block_decode_greedy():
+    """Greedy rounds queued back to back over two passes: tokens, round counts and confidences."""
+    B, K, block, d, V, n_pass = 6, 4, 16, 512, 900, 2
+    dec, ref = _run(B, K, block, d, V, n_pass, 4, seed=88, rho=0.93, greedy=True)
+    X, rounds, sp = dec.tokens.cpu().numpy(), dec.seq_rounds.cpu().numpy(), dec.seq_pass.cpu().numpy()
+    assert np.all(dec.mask.cpu().numpy() == 0) and np.all(sp == n_pass) and np.all(X >= 0)
+    equal = 0
+    for b in range(B):
+        same = np.array_equal(X[b], ref.X[b]) and rounds[b] == ref.rounds[b]
+        equal += int(same)
+        if ref.min_margin[b] < parity.TOL_CDF:
+            continue
+        assert same, (b, X[b], ref.X[b], rounds[b], ref.rounds[b])
+        assert np.allclose(dec.conf.cpu().numpy()[b], ref.conf[b], rtol=2e-4, atol=1e-12)
+    print(f"greedy: {equal}/{B} identical, rounds {rounds.tolist()}", flush=True)
+    assert equal >= B - 1
 
 
 def test_block_decode_llada_shape_rounds_vs_expected_length():

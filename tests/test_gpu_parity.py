@@ -21,7 +21,7 @@ def _np(t):
 def run_case(B, K, block, d, V, dtype="bf16", seed=0, rho=0.9, logit_std=3.0, variant=fb.FEF_GEMM_AUTO,
              temperature=1.0, step=0, seq_base=0, pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0,
              mask=None, pass_mask=None, conf=None, draft_tokens=None, with_logits=True, W=None,
-             hidden=None, logit_atol=2e-4, recorrupt_prob=1.0):
+             hidden=None, logit_atol=2e-4, recorrupt_prob=1.0, greedy=False):
     wl_sigma = logit_std / (0.02 * np.sqrt(d)) if logit_std > 0 else 1.0
     if W is None:
         W = synth.make_head(V, d, seed, dtype)
@@ -34,13 +34,14 @@ def run_case(B, K, block, d, V, dtype="bf16", seed=0, rho=0.9, logit_std=3.0, va
     tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), W.to(DEV), seed, temperature=temperature, step=step,
                        seq_base=seq_base, pos_base=pos_base, n_rm=n_rm, final_pass=final_pass,
                        lowconf_scope=lowconf_scope, mask_in=g_mask, pass_mask=g_pm, conf=g_cf,
-                       draft_tokens=g_dt, recorrupt_prob=recorrupt_prob)
+                       draft_tokens=g_dt, recorrupt_prob=recorrupt_prob, greedy=greedy)
     torch.cuda.synchronize()
     ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), synth.to_f64(W), K, block, seed,
                         temperature=temperature, step=step, seq_base=seq_base, pos_base=pos_base,
                         n_rm=n_rm, final_pass=final_pass, lowconf_scope=lowconf_scope, mask_in=mask,
                         pass_mask=pass_mask, conf=None if conf is None else np.asarray(conf, np.float32),
-                        draft_tokens=draft_tokens, return_logits=with_logits, recorrupt_prob=recorrupt_prob)
+                        draft_tokens=draft_tokens, return_logits=with_logits, recorrupt_prob=recorrupt_prob,
+                        greedy=greedy)
     diag = {k: _np(v) for k, v in vs.diag.items()}
     stats = parity.compare(ref, _np(tok), _np(acc), _np(rem), diag, drafts_given=draft_tokens is not None,
                            logit_atol=logit_atol)
@@ -272,6 +273,55 @@ def test_stochastic_recorruption_of_the_low_confidence_selection():
         counts[prob] = int(out["remask"].sum())
     assert counts[1.0] == 6 * B and counts[5e-8] == 0
     assert counts[1.0] > counts[0.7] > counts[0.3] > 0
+
+
+@pytest.mark.parametrize("B,K,d,V,variant", [(1, 8, 512, 3000, fb.FEF_GEMM_SKINNY), (2, 8, 512, 5003, fb.FEF_GEMM_SKINNY),
+                                             (6, 8, 256, 1500, fb.FEF_GEMM_STREAM128), (24, 4, 128, 999, fb.FEF_GEMM_TILED256),
+                                             (5, 4, 64, 700, fb.FEF_GEMM_TILED), (3, 4, 64, 40, fb.FEF_GEMM_F32)])
+def test_greedy_variant(B, K, d, V, variant):
+    """Zero-temperature variant: arg max drafts, accept on equal arg maxes, corrected token =
+    target arg max, confidences from the finite-temperature softmax; every head kernel's partials."""
+    dtype = "f32" if variant == fb.FEF_GEMM_F32 else "bf16"
+    acc_lens, flipped = [], 0
+    for step, rho in enumerate((0.99, 0.9, 0.6)):
+        ref, out, st = run_case(B, K, 16, d, V, dtype, seed=51, rho=rho, step=step, variant=variant, greedy=True,
+                                temperature=0.8, logit_atol=2e-4 if dtype == "bf16" else 1e-5)
+        flipped += st["near_flipped"]
+        acc_lens += ref.accept_len.tolist()
+    assert flipped <= 1
+    assert min(acc_lens) < K and max(acc_lens) > 0          # both rejections and acceptances occurred
+
+
+def test_greedy_variant_with_supplied_drafts_and_no_uniforms():
+    B, K, d, V = 4, 4, 512, 2000
+    W = synth.make_head(V, d, 3)
+    hidden = synth.make_hidden(B, K, d, 3, 0.9, 3.0 / (0.02 * np.sqrt(d)))
+    a = run_case(B, K, 8, d, V, seed=1, W=W, hidden=hidden, greedy=True, step=0)
+    b = run_case(B, K, 8, d, V, seed=99, W=W, hidden=hidden, greedy=True, step=7, pos_base=64)
+    assert np.array_equal(a[1]["tokens"], b[1]["tokens"]) and np.array_equal(a[1]["accept_len"], b[1]["accept_len"])
+    drafts = a[0].draft_tokens.copy()
+    drafts[:, 1] = (drafts[:, 1] + 1) % V                       # wrong at slot 1 unless it happens to be the target's
+    ref, out, st = run_case(B, K, 8, d, V, seed=1, W=W, hidden=hidden, greedy=True, draft_tokens=drafts.astype(np.int32))
+    assert st["near_flipped"] == 0 and np.all(out["accept_len"] <= 1)
+
+
+def test_greedy_variant_in_split_call_order():
+    """DRAFT call returns the arg max drafts, TARGET call verifies them against the target arg maxes."""
+    B, K, d, V, block = 5, 4, 256, 1200, 8
+    W = synth.make_head(V, d, 4)
+    hd, ht = synth.make_hidden(B, K, d, 4, 0.9, 3.0 / (0.02 * np.sqrt(d)))
+    Wd, hdd, htd = W.to(DEV), hd.to(DEV), ht.to(DEV)
+    vs = fb.VerifyStep(B, K, block, d, V, device=DEV, diag=True, diag_logits=True)
+    tok, _, _ = vs(hdd, None, Wd, 2, step=1, phase=fb.FEF_PHASE_DRAFT, greedy=True)
+    torch.cuda.synchronize()
+    drafts = _np(tok).copy()
+    tok, acc, rem = vs(None, htd, Wd, 2, step=1, phase=fb.FEF_PHASE_TARGET, greedy=True)
+    torch.cuda.synchronize()
+    ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), synth.to_f64(W), K, block, 2, step=1, greedy=True,
+                        return_logits=True)
+    st = parity.compare(ref, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs.diag.items()})
+    clear = ref.argmax_gap[0] >= parity.TOL_ARGMAX
+    assert np.array_equal(drafts[clear], ref.draft_tokens[clear]) and st["near_flipped"] == 0
 
 
 def test_stateful_pass_over_a_block_matches_oracle():
