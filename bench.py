@@ -84,6 +84,65 @@ def cpu_baseline(wl, W, rounds, seed, budget_s=20.0):
                       f"numpy fp64, {el:.1f} s; host has {len(os.sched_getaffinity(0))} usable cores"}
 
 
+def bench_cross_entropy(args, wl, W, Wd, dev):
+    """One step = one fef_head_cross_entropy call on R rows (head kernel without logits store,
+    per-row log-sum-exp merge, loss sum)."""
+    import numpy as np
+    import torch
+    from paper_2605_14305_amd import binding as fb
+    from paper_2605_14305_amd import synth
+    R = args.ce
+    ce = fb.HeadCrossEntropy(R, wl.d, wl.V, dtype=wl.dtype, device=dev)
+    g = torch.Generator().manual_seed(args.seed + 7)
+    hs = [(torch.randn(R, wl.d, generator=g) * wl.sigma_h).to(Wd.dtype).to(dev) for _ in range(4)]
+    labels = torch.randint(0, wl.V, (R,), generator=g, dtype=torch.int32).to(dev)
+    ev = HipEvents()
+    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
+    for i in range(args.warmup):
+        ce(hs[i % 4], Wd, labels)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ce(hs[i % 4], Wd, labels, head_events=pairs[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    head_s = sum(ev.elapsed_ms(a, b) for a, b in pairs) / len(pairs) / 1e3
+    esz = 2 if wl.dtype == "bf16" else 4
+    nT = -(-wl.V // 64)
+    hb = wl.V * wl.d * esz + R * wl.d * esz + R * nT * 8 + R * 4       # no logits are written
+    flops = 2.0 * R * wl.V * wl.d
+    if hb / (HBM_PEAK_GBS * 1e9) >= flops / (MFMA_BF16_PEAK_TFLOPS * 1e12):
+        ach = hb / head_s / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                "traffic": None}
+    else:
+        ach = flops / head_s / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    roof.update({"kernel": "head_stream128_kernel" if R <= 128 else "head_tiled256_kernel",
+                 "avg_kernel_us": head_s * 1e6, "algorithmic_bytes": hb, "flops": flops, "events": "inline"})
+    out = {"metric": "cross-entropy rows/s through the vocabulary head (forward, no logits written)",
+           "value": R / (elapsed / args.steps), "unit": "rows/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+           "config": {"workload": f"ce_{wl.name}_r{R}", "R": R, "d": wl.d, "V": wl.V}, "roofline": roof}
+    if not args.no_cpu_baseline:
+        from oracle import ce_oracle as C
+        W64 = synth.to_f64(W)
+        n = min(R, 16)
+        h64 = synth.to_f64(hs[0][:n])
+        lab = labels[:n].cpu().numpy()
+        t1 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t1 < 10.0 and reps < 16:
+            C.cross_entropy(h64, W64, lab)
+            reps += 1
+        el = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": n * reps / el, "unit": "rows/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": f"{reps} x {n} rows, numpy fp64, {el:.1f} s"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +160,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="record the 16 distinct steps once into a HIP graph and time its replays "
                          "(the head-kernel events then come from a second, eager pass)")
+    ap.add_argument("--ce", type=int, default=0, metavar="R",
+                    help="instead of the verify step, time the cross-entropy use of the head (Algorithm 1's "
+                         "token-level loss, forward only) on R rows of the workload's head shape")
     ap.add_argument("--events", choices=["inline", "separate"], default="inline",
                     help="record the head-kernel events inside the timed steps, or in a second pass")
     args = ap.parse_args()
@@ -126,6 +188,8 @@ def main():
         return
     W = synth.make_head(wl.V, wl.d, args.seed, wl.dtype)
     Wd = W.to(dev)
+    if args.ce:
+        return bench_cross_entropy(args, wl, W, Wd, dev)
     n_rounds = 16   # distinct hidden-state batches, cycled, so only W could ever sit in a cache
     rounds = [synth.make_round(wl, args.seed, block_index=i // 8, step=i) for i in range(n_rounds)]
     rounds_d = [(hd.to(dev), ht.to(dev)) for hd, ht in rounds]

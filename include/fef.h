@@ -54,7 +54,7 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 4
+#define FEF_ABI_VERSION 5
 
 typedef enum {
   FEF_OK = 0,
@@ -177,6 +177,25 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
 /* The head kernel AUTO would choose for these sizes (a fef_gemm_variant), or a negative
  * fef_status.  Pure host function. */
 int32_t fef_select_gemm(const fef_params* prm, int32_t K);
+
+/* Training-side use of the same head (Algorithm 1, position-conditioned training, the
+ * token-level loss CE_{j_m} = -log p_theta(X_0^{j_m} | X^(j_m), t) and its sum over the
+ * prediction positions), forward only.  Row m of h is the predictor's hidden state at position
+ * j_m for the position-conditioned input X^(j_m); p_theta = softmax(h_m W^T / tau).  The head
+ * kernels run with their log-sum-exp epilogue and write no logits at all:
+ *   h         [R, d]  device, dtype prm->dtype, 16-byte aligned
+ *   W_vocab   [V, d]  device, same dtype
+ *   labels    [R]     device int32: the clean token X_0^{j_m}, in [0, V); a negative value marks
+ *                     a row that does not count (its CE is 0).  Values >= V are not detected.
+ *   out_ce    [R]     device float: CE per row
+ *   out_loss  [1]     device float: sum of out_ce in a fixed order; may be NULL
+ * Fields of prm that are read: struct_size, d, V, dtype, temperature, gemm_variant (AUTO,
+ * STREAM128 for R <= 128, TILED256, or F32 for f32 inputs), workspace, workspace_bytes (at least
+ * fef_cross_entropy_workspace_bytes), stream, ev_head_begin / ev_head_end.  Same conventions and
+ * error behaviour as fef_verify_step. */
+size_t fef_cross_entropy_workspace_bytes(const fef_params* prm, int32_t R);
+fef_status fef_head_cross_entropy(const fef_params* prm, const void* h, const void* W_vocab,
+                                  const int32_t* labels, int32_t R, float* out_ce, float* out_loss);
 
 /* Philox4x32-10 word 0 -> uniform, evaluated on the host with the same code the kernels
  * use; lets callers and tests reproduce a draw.  Pure host function. */

@@ -21,7 +21,8 @@ FEF_MAX_K, FEF_MAX_BLOCK = 64, 4096
 FEF_PHASE_FUSED, FEF_PHASE_DRAFT, FEF_PHASE_TARGET = 0, 1, 2
 
 EXPORTS = ["fef_workspace_bytes", "fef_verify_step", "fef_select_gemm", "fef_uniform",
-           "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe"]
+           "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe",
+           "fef_cross_entropy_workspace_bytes", "fef_head_cross_entropy"]
 
 
 class fef_params(ctypes.Structure):
@@ -84,6 +85,11 @@ def lib():
         L.fef_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.fef_abi_version.restype = ctypes.c_int32
         L.fef_abi_version.argtypes = []
+        L.fef_cross_entropy_workspace_bytes.restype = ctypes.c_size_t
+        L.fef_cross_entropy_workspace_bytes.argtypes = [ctypes.POINTER(fef_params), ctypes.c_int32]
+        L.fef_head_cross_entropy.restype = ctypes.c_int
+        L.fef_head_cross_entropy.argtypes = [ctypes.POINTER(fef_params), ctypes.c_void_p, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -138,6 +144,45 @@ def fef_copy_probe(dst, src):
                              ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     if s != FEF_OK:
         raise FefError(s, fef_last_error())
+
+
+class HeadCrossEntropy:
+    """Token-level cross-entropy of R rows through the vocabulary head (fef_head_cross_entropy);
+    holds workspace and outputs of one shape so that repeated calls do no allocation."""
+
+    def __init__(self, R, d, V, dtype="bf16", device="cuda", gemm_variant=FEF_GEMM_AUTO):
+        self.R, self.d, self.V, self.device = R, d, V, torch.device(device)
+        self.dtype = FEF_BF16 if dtype == "bf16" else FEF_F32
+        self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.gemm_variant = gemm_variant
+        n = lib().fef_cross_entropy_workspace_bytes(ctypes.byref(self._params()), R)
+        if n == 0:
+            raise FefError(FEF_ERR_INVALID_ARG, fef_last_error())
+        self.workspace = torch.empty(n, dtype=torch.uint8, device=self.device)
+        self.out_ce = torch.empty(R, dtype=torch.float32, device=self.device)
+        self.out_loss = torch.empty(1, dtype=torch.float32, device=self.device)
+
+    def _params(self, temperature=1.0):
+        return make_params(1, self.d, self.V, dtype=self.dtype, temperature=temperature,
+                           gemm_variant=self.gemm_variant)
+
+    def __call__(self, h, W_vocab, labels, temperature=1.0, head_events=None):
+        assert tuple(h.shape) == (self.R, self.d) and tuple(W_vocab.shape) == (self.V, self.d)
+        assert h.dtype == self.torch_dtype and W_vocab.dtype == self.torch_dtype
+        assert labels.dtype == torch.int32 and tuple(labels.shape) == (self.R,)
+        for t in (h, W_vocab, labels):
+            assert t.is_contiguous() and t.device.type == "cuda"
+        p = self._params(temperature)
+        p.workspace = self.workspace.data_ptr()
+        p.workspace_bytes = self.workspace.numel()
+        p.stream = torch.cuda.current_stream(self.device).cuda_stream
+        if head_events is not None:
+            p.ev_head_begin, p.ev_head_end = head_events
+        s = lib().fef_head_cross_entropy(ctypes.byref(p), _ptr(h), _ptr(W_vocab), _ptr(labels), self.R,
+                                         _ptr(self.out_ce), _ptr(self.out_loss))
+        if s != FEF_OK:
+            raise FefError(s, fef_last_error())
+        return self.out_ce, self.out_loss
 
 
 class VerifyStep:

@@ -1,0 +1,61 @@
+// Finish of the cross-entropy use of the vocabulary head (Algorithm 1, token-level loss):
+// CE_m = log sum_v exp(L[m, v]) - L[m, label_m], loss = sum_m CE_m.  The head kernels have left
+// per (row, vocabulary tile) partials (max, sum exp) and the label token's logit per row; no
+// logits exist in memory.  Fixed reduction trees: the results are reproducible bit for bit.
+#include <math.h>
+
+#include "fef_device.hpp"
+#include "wave_ops.hpp"
+
+namespace fef {
+namespace {
+
+constexpr int NT = 256, NW = NT / kWave;
+
+// one wavefront per row
+__global__ __launch_bounds__(NT) void ce_row_kernel(CeArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * NW + wave;
+  if (r >= a.R) return;
+  const int lab = a.labels[r];
+  float ce = 0.f;
+  if (lab >= 0) {  // wavefront-uniform
+    const float2* P = a.partials + (size_t)r * a.nT;
+    float mx = -INFINITY;
+    for (int t = lane; t < a.nT; t += kWave) mx = fmaxf(mx, P[t].x);
+    mx = wave_max(mx);
+    float sm = 0.f;
+    for (int t = lane; t < a.nT; t += kWave) {
+      const float2 p = P[t];
+      sm += p.y * expf(p.x - mx);
+    }
+    sm = wave_sum(sm);
+    ce = mx + logf(sm) - a.label_logit[r];
+  }
+  if (lane == 0) a.out_ce[r] = ce;
+}
+
+// one workgroup: thread t sums rows t, t + 256, ... in order, then a fixed tree over the threads
+__global__ __launch_bounds__(NT) void ce_sum_kernel(CeArgs a) {
+  __shared__ float part[NW];
+  float s = 0.f;
+  for (int r = threadIdx.x; r < a.R; r += NT) s += a.out_ce[r];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < NW; ++w) t += part[w];
+    a.out_loss[0] = t;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_ce_finish(const CeArgs& a) {
+  hipLaunchKernelGGL(ce_row_kernel, dim3((a.R + NW - 1) / NW), dim3(NT), 0, a.stream, a);
+  if (a.out_loss) hipLaunchKernelGGL(ce_sum_kernel, dim3(1), dim3(NT), 0, a.stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace fef

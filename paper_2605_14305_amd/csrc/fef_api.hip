@@ -185,7 +185,7 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   char* ws = (char*)prm->workspace;
   hipStream_t stream = (hipStream_t)prm->stream;
 
-  fef::HeadArgs h;
+  fef::HeadArgs h{};
   h.h_draft = h_draft; h.h_target = h_target; h.W = W_vocab;
   h.BK = prm->B * K; h.d = prm->d; h.V = prm->V;
   h.row0 = phase == FEF_PHASE_TARGET ? h.BK : 0;
@@ -235,6 +235,94 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   v.stream = stream;
   e = fef::launch_verify(v);
   if (e != hipSuccess) return fail(FEF_ERR_HIP, "verify kernel launch: %s", hipGetErrorString(e));
+  return FEF_OK;
+}
+
+namespace {
+// sizes and kernel choice of a cross-entropy call; *variant receives the head kernel
+fef_status ce_check(const fef_params* p, int32_t R, int* variant, int* nT, size_t* total) {
+  if (!p) return fail(FEF_ERR_INVALID_ARG, "params is NULL");
+  if (p->struct_size != sizeof(fef_params))
+    return fail(FEF_ERR_INVALID_ARG, "struct_size %u does not match this library's %zu", p->struct_size,
+                sizeof(fef_params));
+  if (R < 1 || R > (1 << 24)) return fail(FEF_ERR_INVALID_ARG, "R = %d out of range [1, 2^24]", R);
+  if (p->V < 1 || p->d < 1) return fail(FEF_ERR_INVALID_ARG, "V and d must be positive");
+  if (p->dtype != FEF_BF16 && p->dtype != FEF_F32) return fail(FEF_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
+  if (p->dtype == FEF_BF16 && p->d % 64 != 0)
+    return fail(FEF_ERR_INVALID_ARG, "bf16 needs d to be a multiple of 64 (got %d)", p->d);
+  if (!(p->temperature > 0.f) || !(p->temperature < INFINITY))
+    return fail(FEF_ERR_INVALID_ARG, "temperature must be positive and finite");
+  int v = p->gemm_variant;
+  if (v == FEF_GEMM_AUTO)
+    v = p->dtype == FEF_F32 ? FEF_GEMM_F32 : R <= 128 ? FEF_GEMM_STREAM128 : FEF_GEMM_TILED256;
+  switch (v) {
+    case FEF_GEMM_F32:
+      if (p->dtype != FEF_F32) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel needs dtype f32");
+      if (R > 65535) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel serves at most 65535 rows");
+      break;
+    case FEF_GEMM_STREAM128:
+      if (p->dtype != FEF_BF16 || !fef::stream128_supports(R, p->d))
+        return fail(FEF_ERR_UNSUPPORTED, "streaming head kernel needs bf16 and at most 128 rows");
+      break;
+    case FEF_GEMM_TILED256:
+      if (p->dtype != FEF_BF16) return fail(FEF_ERR_UNSUPPORTED, "tiled head kernels are bf16 only");
+      break;
+    default:
+      return fail(FEF_ERR_UNSUPPORTED, "cross-entropy runs through the F32, STREAM128 or TILED256 head kernel");
+  }
+  *variant = v;
+  *nT = (p->V + fef::kTiledTn - 1) / fef::kTiledTn;
+  *total = align_up((size_t)R * (size_t)*nT * sizeof(float2), 256) + align_up((size_t)R * sizeof(float), 256);
+  return FEF_OK;
+}
+}  // namespace
+
+size_t fef_cross_entropy_workspace_bytes(const fef_params* prm, int32_t R) {
+  int v, nT;
+  size_t total;
+  return ce_check(prm, R, &v, &nT, &total) == FEF_OK ? total : 0;
+}
+
+fef_status fef_head_cross_entropy(const fef_params* prm, const void* h, const void* W_vocab,
+                                  const int32_t* labels, int32_t R, float* out_ce, float* out_loss) {
+  int variant, nT;
+  size_t total;
+  fef_status s = ce_check(prm, R, &variant, &nT, &total);
+  if (s != FEF_OK) return s;
+  if (!h || !W_vocab || !labels || !out_ce)
+    return fail(FEF_ERR_INVALID_ARG, "h, W_vocab, labels and out_ce must not be NULL");
+  if (((uintptr_t)h | (uintptr_t)W_vocab) & 15)
+    return fail(FEF_ERR_INVALID_ARG, "h and W_vocab must be 16-byte aligned");
+  if (!prm->ev_head_begin != !prm->ev_head_end)
+    return fail(FEF_ERR_INVALID_ARG, "ev_head_begin and ev_head_end must be given together");
+  if (!prm->workspace) return fail(FEF_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", total);
+  if ((uintptr_t)prm->workspace & 255) return fail(FEF_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (prm->workspace_bytes < total)
+    return fail(FEF_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", prm->workspace_bytes, total);
+
+  char* ws = (char*)prm->workspace;
+  fef::HeadArgs a{};
+  a.h_draft = h; a.h_target = h; a.W = W_vocab;
+  a.BK = R; a.d = prm->d; a.V = prm->V; a.row0 = 0; a.nrows = R;
+  a.inv_tau = 1.0f / prm->temperature;
+  a.logits = nullptr; a.ldl = 0;
+  a.partials = (float2*)ws; a.nT = nT;
+  a.labels = labels;
+  a.label_logit = (float*)(ws + align_up((size_t)R * (size_t)nT * sizeof(float2), 256));
+  a.stream = (hipStream_t)prm->stream;
+  a.ev_begin = (hipEvent_t)prm->ev_head_begin; a.ev_end = (hipEvent_t)prm->ev_head_end;
+  hipError_t e;
+  switch (variant) {
+    case FEF_GEMM_TILED256: e = fef::launch_head_tiled256(a); break;
+    case FEF_GEMM_STREAM128: e = fef::launch_head_stream128(a); break;
+    default: e = fef::launch_head_f32(a); break;
+  }
+  if (e != hipSuccess) return fail(FEF_ERR_HIP, "head kernel launch: %s", hipGetErrorString(e));
+  fef::CeArgs c{};
+  c.R = R; c.nT = nT; c.partials = a.partials; c.labels = labels; c.label_logit = a.label_logit;
+  c.out_ce = out_ce; c.out_loss = out_loss; c.stream = a.stream;
+  e = fef::launch_ce_finish(c);
+  if (e != hipSuccess) return fail(FEF_ERR_HIP, "cross-entropy kernel launch: %s", hipGetErrorString(e));
   return FEF_OK;
 }
 

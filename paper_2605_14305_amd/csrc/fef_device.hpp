@@ -57,6 +57,10 @@ struct HeadArgs {
   long ldl;
   float2* partials;      // [nrows, nT]: already points at row row0
   int nT;                // partial tiles per row
+  // Cross-entropy use of the head (labels != NULL): no logits are written (logits == NULL) and
+  // the scaled logit of each row's label token goes to label_logit[row].
+  const int32_t* labels;  // [nrows] token id per row, negative = row does not count
+  float* label_logit;     // [nrows]
   hipStream_t stream;
   hipEvent_t ev_begin, ev_end;  // optional: receive the kernel's own start / stop timestamps
 };
@@ -126,5 +130,18 @@ struct VerifyArgs {
 };
 
 hipError_t launch_verify(const VerifyArgs& a);
+
+// Cross-entropy finish: per-row log-sum-exp from the partials, ce = lse - label logit, then the
+// sum over rows in a fixed order.
+struct CeArgs {
+  int R, nT;
+  const float2* partials;   // [R, nT]
+  const int32_t* labels;    // [R]
+  const float* label_logit; // [R]
+  float* out_ce;            // [R]
+  float* out_loss;          // [1]
+  hipStream_t stream;
+};
+hipError_t launch_ce_finish(const CeArgs& a);
 
 }  // namespace fef

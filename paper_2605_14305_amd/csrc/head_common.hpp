@@ -109,7 +109,10 @@ __device__ inline float max_ror(float x) {
 // full 128-byte lines, and the (max, sum exp) over the 64 tokens is a reduction over those 32
 // lanes (four DPP steps inside rows of 16 lanes and one swap of the two rows).  No LDS, and no
 // branch in the interior tiles, so the 16 NI independent (row tile, r) chains interleave freely.
-template <int NI>
+//
+// CE = true is the cross-entropy use of the head: nothing is written but the partials and, for
+// the lane that holds a row's label token, that token's scaled logit.
+template <int NI, bool CE = false>
 __device__ inline void store_logits_and_partials(const HeadArgs& a, floatx16 (&acc)[NI][2], int mw, int vbase,
                                                  int M, int lane) {
   constexpr float kLog2e = 1.4426950408889634f;
@@ -117,7 +120,7 @@ __device__ inline void store_logits_and_partials(const HeadArgs& a, floatx16 (&a
   const float sc = a.inv_tau;
   const int ptile = vbase / kTiledTn;
   const int v0 = vbase + j32, v1 = v0 + 32;
-  float* lbase = a.logits + (size_t)(mw + 4 * h) * a.ldl + v0;
+  float* lbase = CE ? nullptr : a.logits + (size_t)(mw + 4 * h) * a.ldl + v0;
   float2* pbase = a.partials + (size_t)(mw + 4 * h) * a.nT + ptile;
   if (mw + 32 * NI <= M && vbase + 64 <= a.V) {  // interior: wavefront-uniform
 #pragma unroll
@@ -131,9 +134,16 @@ __device__ inline void store_logits_and_partials(const HeadArgs& a, floatx16 (&a
         const float l0 = acc[i][0][r] * sc, l1 = acc[i][1][r] * sc;
         acc[i][0][r] = l0;
         acc[i][1][r] = l1;
-        float* dst = lbase + (size_t)mr * a.ldl;
-        dst[0] = l0;
-        dst[32] = l1;
+        if constexpr (CE) {
+          const int row = mw + 4 * h + mr;
+          const int lab = a.labels[row];
+          if (lab == v0) a.label_logit[row] = l0;
+          if (lab == v1) a.label_logit[row] = l1;
+        } else {
+          float* dst = lbase + (size_t)mr * a.ldl;
+          dst[0] = l0;
+          dst[32] = l1;
+        }
         mx[r] = l0 > l1 ? l0 : l1;
       }
 #pragma unroll
@@ -181,9 +191,16 @@ __device__ inline void store_logits_and_partials(const HeadArgs& a, floatx16 (&a
         const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
         const bool row_ok = mw + 4 * h + mr < M;
         const float l0 = acc[i][0][r] * sc, l1 = acc[i][1][r] * sc;
-        float* dst = lbase + (size_t)mr * a.ldl;
-        if (row_ok && ok0) dst[0] = l0;
-        if (row_ok && ok1) dst[32] = l1;
+        if constexpr (CE) {
+          const int row = mw + 4 * h + mr;
+          const int lab = row_ok ? a.labels[row] : -1;
+          if (ok0 && lab == v0) a.label_logit[row] = l0;
+          if (ok1 && lab == v1) a.label_logit[row] = l1;
+        } else {
+          float* dst = lbase + (size_t)mr * a.ldl;
+          if (row_ok && ok0) dst[0] = l0;
+          if (row_ok && ok1) dst[32] = l1;
+        }
         float mx = row16_max(fmaxf(ok0 ? l0 : -INFINITY, ok1 ? l1 : -INFINITY));
         mx = fmaxf(mx, swap16(mx));  // finite: token vbase itself is valid
         const float mb = mx * kLog2e;

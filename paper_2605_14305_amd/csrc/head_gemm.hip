@@ -412,7 +412,11 @@ __global__ __launch_bounds__(kWave) void head_f32_kernel(HeadArgs a) {
   float acc = 0.f;
   for (int k = 0; k < a.d; ++k) acc = fmaf(hp[k], wp[k], acc);
   const float logit = acc * a.inv_tau;
-  if (valid) a.logits[(size_t)r * a.ldl + v] = logit;
+  if (a.labels) {  // cross-entropy use: keep only the label token's logit
+    if (valid && a.labels[r] == v) a.label_logit[r] = logit;
+  } else if (valid) {
+    a.logits[(size_t)r * a.ldl + v] = logit;
+  }
   float mx = valid ? logit : -INFINITY;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));

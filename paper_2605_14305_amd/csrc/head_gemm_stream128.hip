@@ -34,6 +34,7 @@ struct Frag {
   bf16x8 a[4], b[2];
 };
 
+template <bool CE>
 __global__ __launch_bounds__(512) void head_stream128_kernel(HeadArgs a) {
   __shared__ bf16x8 ringW[kRingW * kStageW];  // 128 KB
   __shared__ bf16x8 ringH[kRingH * kStageH];  // 32 KB: one workgroup per CU
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(512) void head_stream128_kernel(HeadArgs a) {
           keep[t][j][r] = kh == 0 ? acc[t][j][r] + got : got + acc[2 + t][j][r];
         }
   }
-  store_logits_and_partials<2>(a, keep, kh * 64, n0 + wn * 64, M, lane);
+  store_logits_and_partials<2, CE>(a, keep, kh * 64, n0 + wn * 64, M, lane);
 }
 
 }  // namespace
@@ -217,7 +218,8 @@ bool stream128_supports(int M, int d) { return M <= SM && d % 64 == 0; }
 
 hipError_t launch_head_stream128(const HeadArgs& a) {
   const int n_tiles = (a.V + SN - 1) / SN;
-  FEF_LAUNCH_HEAD(head_stream128_kernel, dim3((unsigned)n_tiles), dim3(512), a, a);
+  if (a.labels) FEF_LAUNCH_HEAD(head_stream128_kernel<true>, dim3((unsigned)n_tiles), dim3(512), a, a);
+  else FEF_LAUNCH_HEAD(head_stream128_kernel<false>, dim3((unsigned)n_tiles), dim3(512), a, a);
   return hipGetLastError();
 }
 

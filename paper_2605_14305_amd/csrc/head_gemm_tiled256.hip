@@ -29,7 +29,7 @@ constexpr int kStageChunks = (BM + BN) * 4;  // 16-byte chunks per stage: A rows
 
 // TJ = 32-token tiles per wavefront: 2 -> eight wavefronts of 128 x 64.  (4 -> four wavefronts of
 // 128 x 128, one per SIMD, was measured slower and is not instantiated.)
-template <int TJ>
+template <int TJ, bool CE>
 __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_kernel(HeadArgs a, int m_tiles, int n_tiles) {
   constexpr int WN = BN / (32 * TJ);      // wavefronts along the token dimension
   constexpr int NWAVES = 2 * WN;
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
 
   // Epilogue: logits and per-row (max, sum exp) partials straight from the accumulators.
   static_assert(TJ == 2, "the epilogue covers 64 tokens per wavefront");
-  store_logits_and_partials<4>(a, acc, m0 + wm * 128, n0 + wn * 64, M, lane);
+  store_logits_and_partials<4, CE>(a, acc, m0 + wm * 128, n0 + wn * 64, M, lane);
 }
 
 }  // namespace
@@ -207,7 +207,10 @@ hipError_t launch_head_tiled256(const HeadArgs& a) {
   const int M = a.nrows;
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (a.V + BN - 1) / BN;
   const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
-  FEF_LAUNCH_HEAD(head_tiled256_kernel<2>, dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
+  if (a.labels)
+    FEF_LAUNCH_HEAD((head_tiled256_kernel<2, true>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
+  else
+    FEF_LAUNCH_HEAD((head_tiled256_kernel<2, false>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 

@@ -29,7 +29,7 @@ def test_exports_every_declared_symbol(lib):
     assert declared == set(fb.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.fef_abi_version() == 4
+    assert lib.fef_abi_version() == 5
 
 
 def test_struct_layout_matches(lib):
@@ -120,6 +120,30 @@ def test_argument_validation_happens_on_the_host(lib):
         assert fb.fef_last_error()
     assert lib.fef_status_string(fb.FEF_ERR_WORKSPACE).decode().startswith("workspace")
     assert lib.fef_status_string(0).decode() == "ok"
+
+
+def test_cross_entropy_argument_validation(lib):
+    def call(p, R=4, h=0x1000, w=0x1000, lab=0x1000, out=0x1000):
+        return lib.fef_head_cross_entropy(ctypes.byref(p), ctypes.c_void_p(h), ctypes.c_void_p(w),
+                                          ctypes.c_void_p(lab), R, ctypes.c_void_p(out), None)
+
+    def good(dtype=fb.FEF_BF16, d=64):
+        p = fb.make_params(1, d, 100, dtype=dtype)
+        p.workspace, p.workspace_bytes = 0x10000, 1 << 30
+        return p
+    assert lib.fef_cross_entropy_workspace_bytes(ctypes.byref(good()), 4) >= 4 * 2 * 8 + 16
+    assert lib.fef_cross_entropy_workspace_bytes(ctypes.byref(good()), 0) == 0
+    cases = [(good(), {"R": 0}, fb.FEF_ERR_INVALID_ARG), (good(d=100), {}, fb.FEF_ERR_INVALID_ARG),
+             (good(), {"h": 0}, fb.FEF_ERR_INVALID_ARG), (good(), {"lab": 0}, fb.FEF_ERR_INVALID_ARG),
+             (good(), {"out": 0}, fb.FEF_ERR_INVALID_ARG), (good(), {"w": 0x1004}, fb.FEF_ERR_INVALID_ARG)]
+    p = good(); p.gemm_variant = fb.FEF_GEMM_SKINNY; cases.append((p, {}, fb.FEF_ERR_UNSUPPORTED))
+    p = good(); p.gemm_variant = fb.FEF_GEMM_STREAM128; cases.append((p, {"R": 129}, fb.FEF_ERR_UNSUPPORTED))
+    p = good(); p.gemm_variant = fb.FEF_GEMM_F32; cases.append((p, {}, fb.FEF_ERR_UNSUPPORTED))
+    p = good(); p.temperature = 0.0; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
+    p = good(); p.workspace = 0; cases.append((p, {}, fb.FEF_ERR_WORKSPACE))
+    p = good(); p.workspace_bytes = 8; cases.append((p, {}, fb.FEF_ERR_WORKSPACE))
+    for p, kw, want in cases:
+        assert call(p, **kw) == want, (kw, fb.fef_last_error())
 
 
 def test_library_philox_matches_oracle_philox(lib):
