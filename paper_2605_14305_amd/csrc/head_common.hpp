@@ -113,7 +113,7 @@ __device__ inline float max_ror(float x) {
 // CE = true is the cross-entropy use of the head: nothing is written but the partials and, for
 // the lane that holds a row's label token, that token's scaled logit.
 template <int NI, bool CE = false>
-__device__ inline void store_logits_and_partials(const HeadArgs& a, floatx16 (&acc)[NI][2], int mw, int vbase,
+__device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, floatx16 (&acc)[NI][2], int mw, int vbase,
                                                  int M, int lane) {
   constexpr float kLog2e = 1.4426950408889634f;
   const int j32 = lane & 31, h = lane >> 5;
