@@ -163,6 +163,41 @@ def test_llada_shape_batch8_through_the_streaming_kernel(llada_head):
         print(f"seq {b}: {st}", flush=True)
 
 
+def test_maximum_window_and_block():
+    """K = 64 (the largest window) in a block of 4096 positions (the largest block): window slots by
+    rank over a long mask, LowConf ranking over 4096 candidates, both scopes."""
+    B, K, block, d, V = 3, 64, 4096, 64, 300
+    rng = np.random.default_rng(2)
+    mask = np.zeros((B, block), np.uint8)
+    mask[0, rng.choice(block, size=40, replace=False)] = 1          # fewer than K unresolved: resolves now
+    mask[1, rng.choice(block, size=500, replace=False)] = 1
+    mask[2, :] = 1
+    pm = ((1 - mask) * (rng.random((B, block)) < 0.5)).astype(np.uint8)
+    conf = rng.random((B, block)).astype(np.float32)
+    for scope, n_rm in ((0, 1000), (1, -1)):
+        ref, out, st = run_case(B, K, block, d, V, seed=60 + scope, rho=0.999, logit_std=1.0, mask=mask, pass_mask=pm,
+                                conf=conf, n_rm=n_rm, lowconf_scope=scope, with_logits=False)
+        assert st["near_flipped"] == 0
+        if st["remask_skipped"] == 0:
+            _check_state(ref, out)
+        assert ref.window.tolist() == [40, 64, 64]
+
+
+def test_empty_windows_and_many_sequences():
+    """300 one-token windows, a third of them with nothing left to resolve (empty window: outputs -1,
+    accepted length 0, mask unchanged; with state given, LowConf still fires on a resolved block)."""
+    B, K, block, d, V = 300, 1, 4, 64, 50
+    rng = np.random.default_rng(3)
+    mask = (rng.random((B, block)) < 0.4).astype(np.uint8)
+    mask[::3] = 0
+    ref, out, st = run_case(B, K, block, d, V, seed=70, rho=0.7, mask=mask, final_pass=True, with_logits=False,
+                            variant=fb.FEF_GEMM_TILED256)
+    assert st["near_flipped"] <= 3
+    empty = mask.sum(1) == 0
+    assert empty.sum() >= 100 and np.all(out["tokens"][empty] == -1) and np.all(out["accept_len"][empty] == 0)
+    assert np.all(out["remask"][empty] == 0)
+
+
 def test_very_large_vocabulary_generic_partial_merge():
     # more than 2560 partial tiles and 1024 residual chunks per row: the memory-resident code paths
     ref, out, st = run_case(2, 2, 16, 64, 270001, seed=14, rho=0.8, variant=fb.FEF_GEMM_TILED, with_logits=False)
