@@ -54,7 +54,7 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 5
+#define FEF_ABI_VERSION 6
 
 typedef enum {
   FEF_OK = 0,
@@ -173,6 +173,25 @@ size_t fef_workspace_bytes(const fef_params* prm, int32_t K, int32_t block);
 fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const void* h_target,
                            const void* W_vocab, int32_t K, int32_t block, uint64_t seed,
                            int32_t* out_tokens, int32_t* out_accept_len, uint8_t* out_remask);
+
+/* The decoding step the paper's speed-ups are measured against (Main Results: LLaDA decodes one
+ * token per step, the LLaDA/2 variant two): every window position gets its law from ONE forward,
+ * p = softmax(h[m] W^T / tau); a token is drawn from it (inverse CDF with the draft stream's
+ * uniform, or the arg max when prm->greedy) with confidence p(token); the n_transfer most
+ * confident positions of the window are committed (equal confidences: the lower position first),
+ * the others stay MASK.
+ *   h             [B, K, d]  device: hidden state of window slot m in row m
+ *   out_tokens    [B, K]     committed token of slot m, -1 where the slot was not committed
+ *   out_committed [B]        min(n_transfer, window)
+ *   out_remask    [B, block] unresolved positions after the step
+ * Fields of prm that are read: as in a FEF_PHASE_DRAFT call (which fixes head kernel and workspace
+ * size: fef_workspace_bytes with phase = DRAFT), plus greedy, conf and tokens_state (updated at
+ * the committed positions), diag_draft_tokens (the drawn token of every slot), diag_conf_tok
+ * (its confidence), diag_lse (first B*K entries), diag_logits.  prm->phase must be FUSED (0);
+ * draft_tokens, pass_mask, seq_pass and seq_rounds must be NULL. */
+fef_status fef_topn_step(const fef_params* prm, const void* h, const void* W_vocab, int32_t K, int32_t block,
+                         uint64_t seed, int32_t n_transfer, int32_t* out_tokens, int32_t* out_committed,
+                         uint8_t* out_remask);
 
 /* The head kernel AUTO would choose for these sizes (a fef_gemm_variant), or a negative
  * fef_status.  Pure host function. */

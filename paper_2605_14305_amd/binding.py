@@ -22,7 +22,7 @@ FEF_PHASE_FUSED, FEF_PHASE_DRAFT, FEF_PHASE_TARGET = 0, 1, 2
 
 EXPORTS = ["fef_workspace_bytes", "fef_verify_step", "fef_select_gemm", "fef_uniform",
            "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe",
-           "fef_cross_entropy_workspace_bytes", "fef_head_cross_entropy"]
+           "fef_cross_entropy_workspace_bytes", "fef_head_cross_entropy", "fef_topn_step"]
 
 
 class fef_params(ctypes.Structure):
@@ -87,6 +87,10 @@ def lib():
         L.fef_abi_version.argtypes = []
         L.fef_cross_entropy_workspace_bytes.restype = ctypes.c_size_t
         L.fef_cross_entropy_workspace_bytes.argtypes = [ctypes.POINTER(fef_params), ctypes.c_int32]
+        L.fef_topn_step.restype = ctypes.c_int
+        L.fef_topn_step.argtypes = [ctypes.POINTER(fef_params), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                    ctypes.c_int32, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p]
         L.fef_head_cross_entropy.restype = ctypes.c_int
         L.fef_head_cross_entropy.argtypes = [ctypes.POINTER(fef_params), ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
@@ -272,6 +276,26 @@ class VerifyStep:
         fef_verify_step(p, h_draft, h_target, W_vocab, self.K, self.block, seed, self.out_tokens,
                         self.out_accept_len, self.out_remask)
         return self.out_tokens, self.out_accept_len, self.out_remask
+
+
+def topn_step(vs, h, W_vocab, seed, n_transfer, *, temperature=1.0, step=0, seq_base=0, pos_base=0,
+              mask_in=None, conf=None, tokens_state=None, greedy=False):
+    """Baseline step (fef_topn_step) on the buffers of a VerifyStep of the same shape.  Returns
+    (tokens [B,K], committed [B], remask [B,block])."""
+    assert tuple(h.shape) == (vs.B, vs.K, vs.d) and h.dtype == vs.torch_dtype and h.is_contiguous()
+    p = vs._params(temperature=temperature, step=step, seq_base=seq_base, pos_base=pos_base)
+    p.mask_in = None if mask_in is None else mask_in.data_ptr()
+    p.conf = None if conf is None else conf.data_ptr()
+    p.tokens_state = None if tokens_state is None else tokens_state.data_ptr()
+    p.greedy = int(greedy)
+    p.workspace = vs.workspace.data_ptr()
+    p.workspace_bytes = vs.workspace.numel()
+    p.stream = torch.cuda.current_stream(vs.device).cuda_stream
+    s = lib().fef_topn_step(ctypes.byref(p), _ptr(h), _ptr(W_vocab), vs.K, vs.block, ctypes.c_uint64(seed),
+                            n_transfer, _ptr(vs.out_tokens), _ptr(vs.out_accept_len), _ptr(vs.out_remask))
+    if s != FEF_OK:
+        raise FefError(s, fef_last_error())
+    return vs.out_tokens, vs.out_accept_len, vs.out_remask
 
 
 class BlockDecoder:

@@ -162,14 +162,44 @@ int32_t fef_select_gemm(const fef_params* prm, int32_t K) {
   return s != FEF_OK ? (int32_t)s : v;
 }
 
+namespace {
+constexpr int kPhaseTopN = 3;  // internal: draft rows only, then the baseline's top-n selection
+fef_status run_step(const fef_params* prm, int phase, int n_transfer, const void* h_draft, const void* h_target,
+                    const void* W_vocab, int32_t K, int32_t block, uint64_t seed, int32_t* out_tokens,
+                    int32_t* out_accept_len, uint8_t* out_remask);
+}  // namespace
+
 fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const void* h_target,
                            const void* W_vocab, int32_t K, int32_t block, uint64_t seed,
                            int32_t* out_tokens, int32_t* out_accept_len, uint8_t* out_remask) {
+  if (!prm) return fail(FEF_ERR_INVALID_ARG, "params is NULL");
+  return run_step(prm, prm->phase, 0, h_draft, h_target, W_vocab, K, block, seed, out_tokens, out_accept_len,
+                  out_remask);
+}
+
+fef_status fef_topn_step(const fef_params* prm, const void* h, const void* W_vocab, int32_t K, int32_t block,
+                         uint64_t seed, int32_t n_transfer, int32_t* out_tokens, int32_t* out_committed,
+                         uint8_t* out_remask) {
+  if (!prm) return fail(FEF_ERR_INVALID_ARG, "params is NULL");
+  if (n_transfer < 1) return fail(FEF_ERR_INVALID_ARG, "n_transfer must be at least 1 (got %d)", n_transfer);
+  if (prm->phase != FEF_PHASE_FUSED) return fail(FEF_ERR_INVALID_ARG, "phase must be FUSED (0) in a baseline step");
+  if (prm->draft_tokens || prm->pass_mask || prm->seq_pass || prm->seq_rounds)
+    return fail(FEF_ERR_INVALID_ARG, "draft_tokens, pass_mask, seq_pass and seq_rounds have no meaning in a baseline step");
+  fef_params p = *prm;
+  p.phase = FEF_PHASE_DRAFT;  // sizes, kernel choice and workspace layout of a call over B*K rows
+  return run_step(&p, kPhaseTopN, n_transfer, h, nullptr, W_vocab, K, block, seed, out_tokens, out_committed,
+                  out_remask);
+}
+
+namespace {
+fef_status run_step(const fef_params* prm, int phase, int n_transfer, const void* h_draft, const void* h_target,
+                    const void* W_vocab, int32_t K, int32_t block, uint64_t seed, int32_t* out_tokens,
+                    int32_t* out_accept_len, uint8_t* out_remask) {
   Layout L;
   fef_status s = make_layout(prm, K, block, &L);
   if (s != FEF_OK) return s;
-  const int phase = prm->phase;
-  if ((!h_draft && phase != FEF_PHASE_TARGET) || (!h_target && phase != FEF_PHASE_DRAFT) || !W_vocab)
+  if ((!h_draft && phase != FEF_PHASE_TARGET) || (!h_target && phase != FEF_PHASE_DRAFT && phase != kPhaseTopN) ||
+      !W_vocab)
     return fail(FEF_ERR_INVALID_ARG, "h_draft, h_target and W_vocab must not be NULL");
   if (!out_tokens || ((!out_accept_len || !out_remask) && phase != FEF_PHASE_DRAFT))
     return fail(FEF_ERR_INVALID_ARG, "out_tokens, out_accept_len and out_remask must not be NULL");
@@ -233,10 +263,12 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
   v.diag_resid_mass = prm->diag_resid_mass; v.diag_lse = prm->diag_lse;
   v.diag_logits = prm->diag_logits; v.diag_conf_tok = prm->diag_conf_tok;
   v.stream = stream;
+  v.n_transfer = n_transfer;
   e = fef::launch_verify(v);
   if (e != hipSuccess) return fail(FEF_ERR_HIP, "verify kernel launch: %s", hipGetErrorString(e));
   return FEF_OK;
 }
+}  // namespace
 
 namespace {
 // sizes and kernel choice of a cross-entropy call; *variant receives the head kernel

@@ -92,7 +92,7 @@ struct SeqState {
 struct VerifyArgs {
   int B, K, block, V;
   int row0, nrows;          // logits rows the LSE / draft kernel handles in this call
-  int phase;                // 0 fused, 1 draft half only, 2 target half only
+  int phase;                // 0 fused, 1 draft half only, 2 target half only, 3 baseline top-n step
   long ldl;
   const float* logits;      // [2*B*K, ldl]
   const float2* partials;   // [2*B*K, nT]
@@ -103,6 +103,7 @@ struct VerifyArgs {
   int n_rm, final_pass, lowconf_scope;
   float recorrupt_prob;
   int greedy;
+  int n_transfer;            // baseline step only: positions committed per step
   const uint8_t* mask_in;
   uint8_t* pass_mask;
   float* conf;

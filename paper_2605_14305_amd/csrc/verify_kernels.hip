@@ -663,6 +663,45 @@ __global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
   finalize_sequence(a, b, st, tmp, s_conf, s_mask, s_cand);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Baseline step (parallel prediction with top-n confidence transfer): after kernel 1 has drawn a
+// token for every window slot, one wavefront per sequence takes the confidences p(x) and commits
+// the n most confident slots (equal confidences: the lower position first).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWave) void topn_kernel(VerifyArgs a) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int window = a.window[b];
+  const int s = b * a.K + lane;
+  const bool live = lane < window;
+  int x = -1, pos = INT_MAX;
+  float c = -1.f;
+  if (live) {
+    x = a.xdraft[s];
+    pos = a.slot_pos[s];
+    c = expf(a.logits[(size_t)s * a.ldl + x] - a.lse[s]);
+  }
+  int rank = 0;
+  for (int j = 0; j < window; ++j) {
+    const float cj = __shfl(c, j, 64);
+    const int pj = __shfl(pos, j, 64);
+    rank += (cj > c || (cj == c && pj < pos)) ? 1 : 0;
+  }
+  const bool commit = live && rank < a.n_transfer;
+  const size_t row = (size_t)b * a.block;
+  if (lane < a.K) {
+    a.out_tokens[s] = commit ? x : -1;
+    if (a.diag_conf_tok) a.diag_conf_tok[s] = live ? c : 0.f;
+  }
+  if (lane == 0) a.out_accept_len[b] = min(a.n_transfer, window);
+  for (int i = lane; i < a.block; i += kWave) a.out_remask[row + i] = a.mask_in ? (a.mask_in[row + i] != 0) : 1;
+  __syncthreads();  // one wavefront: orders the mask copy before the committed positions are cleared
+  if (commit) {
+    a.out_remask[row + pos] = 0;
+    if (a.conf) a.conf[row + pos] = c;
+    if (a.tokens_state) a.tokens_state[row + pos] = x;
+  }
+}
+
 __global__ void copy_logits_kernel(const float* __restrict__ src, long ldl, float* __restrict__ dst,
                                    int V, long rows) {
   const long n = rows * V;
@@ -679,7 +718,9 @@ hipError_t launch_verify(const VerifyArgs& a) {
   if (a.nT <= 64 * 4) hipLaunchKernelGGL(row_lse_draft_kernel<4>, g1, dim3(NT), 0, a.stream, a);
   else if (a.nT <= 64 * 40) hipLaunchKernelGGL(row_lse_draft_kernel<40>, g1, dim3(NT), 0, a.stream, a);
   else hipLaunchKernelGGL(row_lse_draft_kernel<0>, g1, dim3(NT), 0, a.stream, a);
-  if (a.phase != 1) {  // everything after the draft sample needs the target laws
+  if (a.phase == 3) {
+    hipLaunchKernelGGL(topn_kernel, dim3(a.B), dim3(kWave), 0, a.stream, a);
+  } else if (a.phase != 1) {  // everything after the draft sample needs the target laws
     const int gx = (a.nRC + NW - 1) / NW;
     const int nslots = a.all_slots ? a.B * a.K : a.B;
     hipLaunchKernelGGL(accept_resid_kernel, dim3(nslots, gx), dim3(NT), 0, a.stream, a);

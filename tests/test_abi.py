@@ -29,7 +29,7 @@ def test_exports_every_declared_symbol(lib):
     assert declared == set(fb.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.fef_abi_version() == 5
+    assert lib.fef_abi_version() == 6
 
 
 def test_struct_layout_matches(lib):
