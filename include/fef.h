@@ -54,7 +54,7 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 6
+#define FEF_ABI_VERSION 7
 
 typedef enum {
   FEF_OK = 0,
@@ -77,8 +77,8 @@ typedef enum {
   FEF_GEMM_TILED = 2,  /* bf16, any M: plain 128x128 LDS-tiled MFMA GEMM (never picked by AUTO) */
   FEF_GEMM_F32 = 3,    /* f32, any shape: reference-grade FMA kernel                       */
   FEF_GEMM_TILED256 = 4, /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)       */
-  FEF_GEMM_STREAM128 = 5 /* bf16, M <= 128: all rows x 256 tokens per workgroup, W streamed
-                            through a six-stage LDS ring (AUTO: 32 < M <= 128)              */
+  FEF_GEMM_STREAM = 5    /* bf16, M <= 128: all rows x 256 tokens per persistent workgroup, W
+                            streamed through a deep LDS ring (AUTO: 32 < M <= 128)          */
 } fef_gemm_variant;
 
 /* In Algorithm 2 the verification inputs X^(j_m) carry the draft prefix, so a real target
@@ -209,7 +209,7 @@ int32_t fef_select_gemm(const fef_params* prm, int32_t K);
  *   out_ce    [R]     device float: CE per row
  *   out_loss  [1]     device float: sum of out_ce in a fixed order; may be NULL
  * Fields of prm that are read: struct_size, d, V, dtype, temperature, gemm_variant (AUTO,
- * STREAM128 for R <= 128, TILED256, or F32 for f32 inputs), workspace, workspace_bytes (at least
+ * STREAM for R <= 128, TILED256, or F32 for f32 inputs), workspace, workspace_bytes (at least
  * fef_cross_entropy_workspace_bytes), stream, ev_head_begin / ev_head_end.  Same conventions and
  * error behaviour as fef_verify_step. */
 size_t fef_cross_entropy_workspace_bytes(const fef_params* prm, int32_t R);

@@ -16,7 +16,7 @@ FEF_ERR_UNSUPPORTED = -2
 FEF_ERR_WORKSPACE = -3
 FEF_ERR_HIP = -4
 FEF_BF16, FEF_F32 = 0, 1
-FEF_GEMM_AUTO, FEF_GEMM_SKINNY, FEF_GEMM_TILED, FEF_GEMM_F32, FEF_GEMM_TILED256, FEF_GEMM_STREAM128 = 0, 1, 2, 3, 4, 5
+FEF_GEMM_AUTO, FEF_GEMM_SKINNY, FEF_GEMM_TILED, FEF_GEMM_F32, FEF_GEMM_TILED256, FEF_GEMM_STREAM = 0, 1, 2, 3, 4, 5
 FEF_MAX_K, FEF_MAX_BLOCK = 64, 4096
 FEF_PHASE_FUSED, FEF_PHASE_DRAFT, FEF_PHASE_TARGET = 0, 1, 2
 

@@ -67,7 +67,7 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
   if (v == FEF_GEMM_AUTO) {
     if (p->dtype == FEF_F32) v = FEF_GEMM_F32;
     else if (fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d)) v = FEF_GEMM_SKINNY;
-    else v = M > 128 ? FEF_GEMM_TILED256 : FEF_GEMM_STREAM128;
+    else v = M > 128 ? FEF_GEMM_TILED256 : FEF_GEMM_STREAM;
   }
   switch (v) {
     case FEF_GEMM_SKINNY:
@@ -78,8 +78,8 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
     case FEF_GEMM_TILED256:
       if (p->dtype != FEF_BF16) return fail(FEF_ERR_UNSUPPORTED, "tiled head kernels are bf16 only");
       break;
-    case FEF_GEMM_STREAM128:
-      if (p->dtype != FEF_BF16 || !fef::stream128_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d))
+    case FEF_GEMM_STREAM:
+      if (p->dtype != FEF_BF16 || !fef::stream_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d))
         return fail(FEF_ERR_UNSUPPORTED, "streaming head kernel needs bf16 and at most 128 rows through the head");
       break;
     case FEF_GEMM_F32:
@@ -230,7 +230,7 @@ fef_status run_step(const fef_params* prm, int phase, int n_transfer, const void
     case FEF_GEMM_SKINNY: e = fef::launch_head_skinny(h); break;
     case FEF_GEMM_TILED: e = fef::launch_head_tiled(h); break;
     case FEF_GEMM_TILED256: e = fef::launch_head_tiled256(h); break;
-    case FEF_GEMM_STREAM128: e = fef::launch_head_stream128(h); break;
+    case FEF_GEMM_STREAM: e = fef::launch_head_stream(h); break;
     default: e = fef::launch_head_f32(h); break;
   }
   if (e != hipSuccess) return fail(FEF_ERR_HIP, "head kernel launch: %s", hipGetErrorString(e));
@@ -286,21 +286,21 @@ fef_status ce_check(const fef_params* p, int32_t R, int* variant, int* nT, size_
     return fail(FEF_ERR_INVALID_ARG, "temperature must be positive and finite");
   int v = p->gemm_variant;
   if (v == FEF_GEMM_AUTO)
-    v = p->dtype == FEF_F32 ? FEF_GEMM_F32 : R <= 128 ? FEF_GEMM_STREAM128 : FEF_GEMM_TILED256;
+    v = p->dtype == FEF_F32 ? FEF_GEMM_F32 : R <= 128 ? FEF_GEMM_STREAM : FEF_GEMM_TILED256;
   switch (v) {
     case FEF_GEMM_F32:
       if (p->dtype != FEF_F32) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel needs dtype f32");
       if (R > 65535) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel serves at most 65535 rows");
       break;
-    case FEF_GEMM_STREAM128:
-      if (p->dtype != FEF_BF16 || !fef::stream128_supports(R, p->d))
+    case FEF_GEMM_STREAM:
+      if (p->dtype != FEF_BF16 || !fef::stream_supports(R, p->d))
         return fail(FEF_ERR_UNSUPPORTED, "streaming head kernel needs bf16 and at most 128 rows");
       break;
     case FEF_GEMM_TILED256:
       if (p->dtype != FEF_BF16) return fail(FEF_ERR_UNSUPPORTED, "tiled head kernels are bf16 only");
       break;
     default:
-      return fail(FEF_ERR_UNSUPPORTED, "cross-entropy runs through the F32, STREAM128 or TILED256 head kernel");
+      return fail(FEF_ERR_UNSUPPORTED, "cross-entropy runs through the F32, STREAM or TILED256 head kernel");
   }
   *variant = v;
   *nT = (p->V + fef::kTiledTn - 1) / fef::kTiledTn;
@@ -346,7 +346,7 @@ fef_status fef_head_cross_entropy(const fef_params* prm, const void* h, const vo
   hipError_t e;
   switch (variant) {
     case FEF_GEMM_TILED256: e = fef::launch_head_tiled256(a); break;
-    case FEF_GEMM_STREAM128: e = fef::launch_head_stream128(a); break;
+    case FEF_GEMM_STREAM: e = fef::launch_head_stream(a); break;
     default: e = fef::launch_head_f32(a); break;
   }
   if (e != hipSuccess) return fail(FEF_ERR_HIP, "head kernel launch: %s", hipGetErrorString(e));

@@ -74,8 +74,8 @@ bool skinny_supports(int M, int d);
 hipError_t launch_head_skinny(const HeadArgs& a);
 hipError_t launch_head_tiled(const HeadArgs& a);
 hipError_t launch_head_tiled256(const HeadArgs& a);
-bool stream128_supports(int M, int d);
-hipError_t launch_head_stream128(const HeadArgs& a);
+bool stream_supports(int M, int d);
+hipError_t launch_head_stream(const HeadArgs& a);
 hipError_t launch_head_f32(const HeadArgs& a);
 
 // ---------------------------------------------------------------------------------------------

@@ -38,7 +38,7 @@ struct Frag {
 };
 
 template <bool CE>
-__global__ __launch_bounds__(512) void head_stream128_kernel(HeadArgs a, int n_tiles) {
+__global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tiles) {
   __shared__ bf16x8 ringW[kRingW * kStageW];  // 128 KB
   __shared__ bf16x8 ringH[kRingH * kStageH];  // 32 KB: one workgroup per CU
   const int tid = threadIdx.x, lane = tid & 63;
@@ -228,9 +228,9 @@ __global__ __launch_bounds__(512) void head_stream128_kernel(HeadArgs a, int n_t
 
 }  // namespace
 
-bool stream128_supports(int M, int d) { return M <= SM && d % 64 == 0; }
+bool stream_supports(int M, int d) { return M <= SM && d % 64 == 0; }
 
-hipError_t launch_head_stream128(const HeadArgs& a) {
+hipError_t launch_head_stream(const HeadArgs& a) {
   const int n_tiles = (a.V + SN - 1) / SN;
   // one workgroup per CU (the kernel uses all of a CU's LDS); each walks its tiles back to back
   static int cus[64];
@@ -245,8 +245,8 @@ hipError_t launch_head_stream128(const HeadArgs& a) {
     cus[dev] = n > 0 ? n : 1;
   }
   const int grid = n_tiles < cus[dev] ? n_tiles : cus[dev];
-  if (a.labels) FEF_LAUNCH_HEAD(head_stream128_kernel<true>, dim3((unsigned)grid), dim3(512), a, a, n_tiles);
-  else FEF_LAUNCH_HEAD(head_stream128_kernel<false>, dim3((unsigned)grid), dim3(512), a, a, n_tiles);
+  if (a.labels) FEF_LAUNCH_HEAD(head_stream_kernel<true>, dim3((unsigned)grid), dim3(512), a, a, n_tiles);
+  else FEF_LAUNCH_HEAD(head_stream_kernel<false>, dim3((unsigned)grid), dim3(512), a, a, n_tiles);
   return hipGetLastError();
 }
 

@@ -29,7 +29,7 @@ def test_exports_every_declared_symbol(lib):
     assert declared == set(fb.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.fef_abi_version() == 6
+    assert lib.fef_abi_version() == 7
 
 
 def test_struct_layout_matches(lib):
@@ -55,11 +55,11 @@ def test_gemm_selection(lib):
     assert fb.fef_select_gemm(fb.make_params(1, 3584, 151936), 8) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(1, 4096, 126464), 16) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(2, 4096, 126464), 8) == fb.FEF_GEMM_SKINNY
-    assert fb.fef_select_gemm(fb.make_params(3, 4096, 126464), 8) == fb.FEF_GEMM_STREAM128
+    assert fb.fef_select_gemm(fb.make_params(3, 4096, 126464), 8) == fb.FEF_GEMM_STREAM
     assert fb.fef_select_gemm(fb.make_params(16, 4096, 126464), 8) == fb.FEF_GEMM_TILED256
-    assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_STREAM128
-    assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_STREAM128
-    p = fb.make_params(9, 4096, 126464, gemm_variant=fb.FEF_GEMM_STREAM128)
+    assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_STREAM
+    assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_STREAM
+    p = fb.make_params(9, 4096, 126464, gemm_variant=fb.FEF_GEMM_STREAM)
     assert fb.fef_select_gemm(p, 8) == fb.FEF_ERR_UNSUPPORTED
     assert fb.fef_select_gemm(fb.make_params(1, 64, 32, dtype=fb.FEF_F32), 4) == fb.FEF_GEMM_F32
     p = fb.make_params(16, 4096, 126464, gemm_variant=fb.FEF_GEMM_SKINNY)
@@ -137,7 +137,7 @@ def test_cross_entropy_argument_validation(lib):
              (good(), {"h": 0}, fb.FEF_ERR_INVALID_ARG), (good(), {"lab": 0}, fb.FEF_ERR_INVALID_ARG),
              (good(), {"out": 0}, fb.FEF_ERR_INVALID_ARG), (good(), {"w": 0x1004}, fb.FEF_ERR_INVALID_ARG)]
     p = good(); p.gemm_variant = fb.FEF_GEMM_SKINNY; cases.append((p, {}, fb.FEF_ERR_UNSUPPORTED))
-    p = good(); p.gemm_variant = fb.FEF_GEMM_STREAM128; cases.append((p, {"R": 129}, fb.FEF_ERR_UNSUPPORTED))
+    p = good(); p.gemm_variant = fb.FEF_GEMM_STREAM; cases.append((p, {"R": 129}, fb.FEF_ERR_UNSUPPORTED))
     p = good(); p.gemm_variant = fb.FEF_GEMM_F32; cases.append((p, {}, fb.FEF_ERR_UNSUPPORTED))
     p = good(); p.temperature = 0.0; cases.append((p, {}, fb.FEF_ERR_INVALID_ARG))
     p = good(); p.workspace = 0; cases.append((p, {}, fb.FEF_ERR_WORKSPACE))

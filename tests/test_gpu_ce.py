@@ -39,7 +39,7 @@ def _check(got, loss, h, W, labels, temperature=1.0, rows=None):
     return want
 
 
-@pytest.mark.parametrize("R,d,V,variant", [(5, 64, 1000, fb.FEF_GEMM_STREAM128), (128, 256, 777, fb.FEF_GEMM_STREAM128),
+@pytest.mark.parametrize("R,d,V,variant", [(5, 64, 1000, fb.FEF_GEMM_STREAM), (128, 256, 777, fb.FEF_GEMM_STREAM),
                                            (33, 512, 2050, fb.FEF_GEMM_AUTO), (300, 128, 999, fb.FEF_GEMM_AUTO),
                                            (129, 64, 65, fb.FEF_GEMM_TILED256), (1, 64, 1, fb.FEF_GEMM_TILED256),
                                            (700, 1024, 3001, fb.FEF_GEMM_TILED256)])

@@ -137,11 +137,11 @@ def test_tiled256_kernel_small_shapes(B, K, d, V):
 
 
 @pytest.mark.parametrize("B,K,d,V", [(5, 8, 64, 1000), (3, 5, 128, 777), (8, 8, 512, 2050), (1, 1, 64, 1),
-                                     (4, 16, 256, 300), (2, 9, 3584, 1500), (6, 8, 1024, 513)])
-def test_stream128_kernel_small_shapes(B, K, d, V):
+                                     (4, 16, 256, 300), (2, 9, 3584, 1500), (6, 8, 1024, 513), (7, 8, 512, 2049)])
+def test_stream_kernel_small_shapes(B, K, d, V):
     """All rows x 256 tokens per workgroup, k halves added through LDS: 2 to 128 rows through the
     head, k loops of 2 to 112 steps (prologue only, tail only, steady groups plus tail), ragged V."""
-    ref, out, st = run_case(B, K, max(K, 16), d, V, seed=16, rho=0.8, variant=fb.FEF_GEMM_STREAM128)
+    ref, out, st = run_case(B, K, max(K, 16), d, V, seed=16, rho=0.8, variant=fb.FEF_GEMM_STREAM)
     assert st["near_flipped"] <= B // 20
 
 
@@ -151,7 +151,7 @@ def test_llada_shape_batch8_through_the_streaming_kernel(llada_head):
     wl, W, Wd, W64 = llada_head
     B, K, block = 8, 8, 32
     vs = fb.VerifyStep(B, K, block, wl.d, wl.V, device=DEV, diag=True)
-    assert fb.fef_select_gemm(vs._params(), K) == fb.FEF_GEMM_STREAM128
+    assert fb.fef_select_gemm(vs._params(), K) == fb.FEF_GEMM_STREAM
     hd, ht = synth.make_hidden(B, K, wl.d, 9, wl.rho, wl.sigma_h, "bf16", 0, 2)
     tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 9, step=2)
     torch.cuda.synchronize()
@@ -217,7 +217,7 @@ def test_skinny_and_tiled_agree():
 def test_deterministic_bits():
     W = synth.make_head(5000, 512, 1).to(DEV)
     hd, ht = (t.to(DEV) for t in synth.make_hidden(2, 4, 512, 1, 0.8, 3.0 / (0.02 * np.sqrt(512))))
-    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED, fb.FEF_GEMM_TILED256, fb.FEF_GEMM_STREAM128):
+    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED, fb.FEF_GEMM_TILED256, fb.FEF_GEMM_STREAM):
         outs = []
         for rep in range(3):
             vs = fb.VerifyStep(2, 4, 8, 512, 5000, diag=True, diag_logits=True, gemm_variant=variant)
@@ -311,7 +311,7 @@ def test_stochastic_recorruption_of_the_low_confidence_selection():
 
 
 @pytest.mark.parametrize("B,K,d,V,variant", [(1, 8, 512, 3000, fb.FEF_GEMM_SKINNY), (2, 8, 512, 5003, fb.FEF_GEMM_SKINNY),
-                                             (6, 8, 256, 1500, fb.FEF_GEMM_STREAM128), (24, 4, 128, 999, fb.FEF_GEMM_TILED256),
+                                             (6, 8, 256, 1500, fb.FEF_GEMM_STREAM), (24, 4, 128, 999, fb.FEF_GEMM_TILED256),
                                              (5, 4, 64, 700, fb.FEF_GEMM_TILED), (3, 4, 64, 40, fb.FEF_GEMM_F32)])
 def test_greedy_variant(B, K, d, V, variant):
     """Zero-temperature variant: arg max drafts, accept on equal arg maxes, corrected token =
