@@ -205,7 +205,7 @@ int32_t fef_select_gemm(const fef_params* prm, int32_t K);
  *   h         [R, d]  device, dtype prm->dtype, 16-byte aligned
  *   W_vocab   [V, d]  device, same dtype
  *   labels    [R]     device int32: the clean token X_0^{j_m}, in [0, V); a negative value marks
- *                     a row that does not count (its CE is 0).  Values >= V are not detected.
+ *                     a row that does not count (its CE is 0).  A value >= V gives CE = NaN.
  *   out_ce    [R]     device float: CE per row
  *   out_loss  [1]     device float: sum of out_ce in a fixed order; may be NULL
  * Fields of prm that are read: struct_size, d, V, dtype, temperature, gemm_variant (AUTO,

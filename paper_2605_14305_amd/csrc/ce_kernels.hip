@@ -12,6 +12,12 @@ namespace {
 
 constexpr int NT = 256, NW = NT / kWave;
 
+// label logits start as NaN, so that a label no head kernel meets (>= V) shows in the result
+__global__ __launch_bounds__(NT) void ce_init_kernel(float* label_logit, int R) {
+  const int r = blockIdx.x * NT + threadIdx.x;
+  if (r < R) label_logit[r] = __builtin_nanf("");
+}
+
 // one wavefront per row
 __global__ __launch_bounds__(NT) void ce_row_kernel(CeArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -51,6 +57,11 @@ __global__ __launch_bounds__(NT) void ce_sum_kernel(CeArgs a) {
 }
 
 }  // namespace
+
+hipError_t launch_ce_init(float* label_logit, int R, hipStream_t stream) {
+  hipLaunchKernelGGL(ce_init_kernel, dim3((R + NT - 1) / NT), dim3(NT), 0, stream, label_logit, R);
+  return hipGetLastError();
+}
 
 hipError_t launch_ce_finish(const CeArgs& a) {
   hipLaunchKernelGGL(ce_row_kernel, dim3((a.R + NW - 1) / NW), dim3(NT), 0, a.stream, a);

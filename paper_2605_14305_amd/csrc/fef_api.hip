@@ -343,7 +343,8 @@ fef_status fef_head_cross_entropy(const fef_params* prm, const void* h, const vo
   a.label_logit = (float*)(ws + align_up((size_t)R * (size_t)nT * sizeof(float2), 256));
   a.stream = (hipStream_t)prm->stream;
   a.ev_begin = (hipEvent_t)prm->ev_head_begin; a.ev_end = (hipEvent_t)prm->ev_head_end;
-  hipError_t e;
+  hipError_t e = fef::launch_ce_init(a.label_logit, R, a.stream);
+  if (e != hipSuccess) return fail(FEF_ERR_HIP, "cross-entropy kernel launch: %s", hipGetErrorString(e));
   switch (variant) {
     case FEF_GEMM_TILED256: e = fef::launch_head_tiled256(a); break;
     case FEF_GEMM_STREAM: e = fef::launch_head_stream(a); break;

@@ -143,6 +143,7 @@ struct CeArgs {
   float* out_loss;          // [1]
   hipStream_t stream;
 };
+hipError_t launch_ce_init(float* label_logit, int R, hipStream_t stream);
 hipError_t launch_ce_finish(const CeArgs& a);
 
 }  // namespace fef

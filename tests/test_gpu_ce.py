@@ -72,6 +72,17 @@ def test_cross_entropy_is_deterministic_and_ignores_stale_workspace():
         assert np.array_equal(o[0], outs[0][0]) and np.array_equal(o[1], outs[0][1])
 
 
+def test_cross_entropy_label_out_of_range_gives_nan():
+    W = synth.make_head(300, 64, 1)
+    ce = fb.HeadCrossEntropy(5, 64, 300, device=DEV)
+    h = torch.ones(5, 64, dtype=torch.bfloat16, device=DEV)
+    lab = torch.tensor([0, 299, 300, 12345, -1], dtype=torch.int32, device=DEV)
+    out, loss = ce(h, W.to(DEV), lab)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert np.isfinite(o[[0, 1, 4]]).all() and o[4] == 0.0 and np.isnan(o[[2, 3]]).all()
+
+
 def test_cross_entropy_llada_shape_sampled_rows():
     """LLaDA-shaped head (d=4096, V=126464), 2048 position-conditioned rows through the 256x256
     kernel and 128 through the streaming kernel; the oracle checks a seeded sample of rows."""
