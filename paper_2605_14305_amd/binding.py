@@ -20,6 +20,8 @@ FEF_GEMM_AUTO, FEF_GEMM_SKINNY, FEF_GEMM_TILED, FEF_GEMM_F32, FEF_GEMM_TILED256,
 FEF_MAX_K, FEF_MAX_BLOCK = 64, 4096
 FEF_PHASE_FUSED, FEF_PHASE_DRAFT, FEF_PHASE_TARGET = 0, 1, 2
 
+ABI_VERSION = 7   # FEF_ABI_VERSION of include/fef.h this binding's fef_params mirrors
+
 EXPORTS = ["fef_workspace_bytes", "fef_verify_step", "fef_select_gemm", "fef_uniform",
            "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe",
            "fef_cross_entropy_workspace_bytes", "fef_head_cross_entropy", "fef_topn_step"]
@@ -94,6 +96,9 @@ def lib():
         L.fef_head_cross_entropy.restype = ctypes.c_int
         L.fef_head_cross_entropy.argtypes = [ctypes.POINTER(fef_params), ctypes.c_void_p, ctypes.c_void_p,
                                              ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        if L.fef_abi_version() != ABI_VERSION:
+            raise RuntimeError(f"{LIB_PATH} has ABI version {L.fef_abi_version()}, this binding needs {ABI_VERSION}: "
+                               "rebuild it with `python -m paper_2605_14305_amd.build`")
         _lib = L
     return _lib
 

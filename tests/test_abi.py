@@ -29,7 +29,13 @@ def test_exports_every_declared_symbol(lib):
     assert declared == set(fb.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.fef_abi_version() == 7
+    assert lib.fef_abi_version() == fb.ABI_VERSION
+    assert f"#define FEF_ABI_VERSION {fb.ABI_VERSION}\n" in open(os.path.join(ROOT, "include", "fef.h")).read()
+
+
+def test_graft_entry_build_compiles_and_loads():
+    import __graft_entry__ as g
+    g.build()
 
 
 def test_struct_layout_matches(lib):
