@@ -112,9 +112,10 @@ __device__ inline float max_ror(float x) {
 //
 // CE = true is the cross-entropy use of the head: nothing is written but the partials and, for
 // the lane that holds a row's label token, that token's scaled logit.
-template <int NI, bool CE = false>
+template <int NI, bool CE = false, int RB = 16>
 __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, floatx16 (&acc)[NI][2], int mw, int vbase,
                                                  int M, int lane) {
+  static_assert(RB == 4 || RB == 8 || RB == 16, "accumulator indices per batch");
   constexpr float kLog2e = 1.4426950408889634f;
   const int j32 = lane & 31, h = lane >> 5;
   const float sc = a.inv_tau;
@@ -125,61 +126,67 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
   if (mw + 32 * NI <= M && vbase + 64 <= a.V) {  // interior: wavefront-uniform
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      // phase by phase over the 16 accumulator indices, so that the 16 reduction chains are
-      // independent neighbours in program order
-      float mx[16], e[16];
+      // phase by phase over RB accumulator indices at a time, so that the RB reduction chains
+      // are independent neighbours in program order (RB = 16 where the epilogue's arithmetic is
+      // on the critical path, less where registers are short)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
-        const float l0 = acc[i][0][r] * sc, l1 = acc[i][1][r] * sc;
-        acc[i][0][r] = l0;
-        acc[i][1][r] = l1;
-        if constexpr (CE) {
-          const int row = mw + 4 * h + mr;
-          const int lab = a.labels[row];
-          if (lab == v0) a.label_logit[row] = l0;
-          if (lab == v1) a.label_logit[row] = l1;
-        } else {
-          float* dst = lbase + (size_t)mr * a.ldl;
-          dst[0] = l0;
-          dst[32] = l1;
+      for (int rb = 0; rb < 16; rb += RB) {
+        float mx[RB], e[RB];
+#pragma unroll
+        for (int q = 0; q < RB; ++q) {
+          const int r = rb + q;
+          const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
+          const float l0 = acc[i][0][r] * sc, l1 = acc[i][1][r] * sc;
+          acc[i][0][r] = l0;
+          acc[i][1][r] = l1;
+          if constexpr (CE) {
+            const int row = mw + 4 * h + mr;
+            const int lab = a.labels[row];
+            if (lab == v0) a.label_logit[row] = l0;
+            if (lab == v1) a.label_logit[row] = l1;
+          } else {
+            float* dst = lbase + (size_t)mr * a.ldl;
+            dst[0] = l0;
+            dst[32] = l1;
+          }
+          mx[q] = l0 > l1 ? l0 : l1;
         }
-        mx[r] = l0 > l1 ? l0 : l1;
-      }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = max_ror<8>(mx[r]);
+        for (int q = 0; q < RB; ++q) mx[q] = max_ror<8>(mx[q]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = max_ror<4>(mx[r]);
+        for (int q = 0; q < RB; ++q) mx[q] = max_ror<4>(mx[q]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = max_ror<2>(mx[r]);
+        for (int q = 0; q < RB; ++q) mx[q] = max_ror<2>(mx[q]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = max_ror<1>(mx[r]);
+        for (int q = 0; q < RB; ++q) mx[q] = max_ror<1>(mx[q]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) e[r] = swap16(mx[r]);
+        for (int q = 0; q < RB; ++q) e[q] = swap16(mx[q]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx[r] = mx[r] > e[r] ? mx[r] : e[r];
+        for (int q = 0; q < RB; ++q) mx[q] = mx[q] > e[q] ? mx[q] : e[q];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float mb = mx[r] * kLog2e;
-        e[r] = __builtin_amdgcn_exp2f(fmaf(acc[i][0][r], kLog2e, -mb)) +
-               __builtin_amdgcn_exp2f(fmaf(acc[i][1][r], kLog2e, -mb));
-      }
+        for (int q = 0; q < RB; ++q) {
+          const float mb = mx[q] * kLog2e;
+          e[q] = __builtin_amdgcn_exp2f(fmaf(acc[i][0][rb + q], kLog2e, -mb)) +
+                 __builtin_amdgcn_exp2f(fmaf(acc[i][1][rb + q], kLog2e, -mb));
+        }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) e[r] += row_ror<8>(e[r]);
+        for (int q = 0; q < RB; ++q) e[q] += row_ror<8>(e[q]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) e[r] += row_ror<4>(e[r]);
+        for (int q = 0; q < RB; ++q) e[q] += row_ror<4>(e[q]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) e[r] += row_ror<2>(e[r]);
+        for (int q = 0; q < RB; ++q) e[q] += row_ror<2>(e[q]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) e[r] += row_ror<1>(e[r]);
-      float t[16];
+        for (int q = 0; q < RB; ++q) e[q] += row_ror<1>(e[q]);
+        float t[RB];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) t[r] = swap16(e[r]);
-      // every lane of a half-wavefront holds its row's pair and writes it to the same address
+        for (int q = 0; q < RB; ++q) t[q] = swap16(e[q]);
+        // every lane of a half-wavefront holds its row's pair and writes it to the same address
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
-        pbase[(size_t)mr * a.nT] = make_float2(mx[r], e[r] + t[r]);
+        for (int q = 0; q < RB; ++q) {
+          const int r = rb + q;
+          const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
+          pbase[(size_t)mr * a.nT] = make_float2(mx[q], e[q] + t[q]);
+        }
       }
     }
   } else if (vbase < a.V) {  // edge tiles: rows past M and tokens past V are masked

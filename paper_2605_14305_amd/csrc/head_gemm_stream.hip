@@ -16,9 +16,17 @@
 // epilogue enter the same counter behind the loads in flight; the waits that follow are by count
 // of the youngest operations, so they can only wait for more than they need, never for less.
 //
-// Eight wavefronts as 2 (64-row halves) x 4 (64-token columns), each 2 x 2
-// v_mfma_f32_32x32x16_bf16 tiles over the full k: eight 16-byte fragment reads for eight
-// multiplies per step, and a tile ends in the shared epilogue with no exchange between wavefronts.
+// Eight wavefronts as 2 (row halves) x 4 (64-token columns), each NI x 2
+// v_mfma_f32_32x32x16_bf16 tiles over the full k (NI = 2: 128 rows per tile, eight 16-byte
+// fragment reads for eight multiplies per step; NI = 1 for M <= 64: 64 rows, half the multiplies,
+// which at these sizes is less heat rather than less time: the kernel runs against the power
+// limit, and the memory system slows down with the clocks), and a tile ends in the shared
+// epilogue with no exchange between wavefronts.
+//
+// Each workgroup starts its walk over k at another k-step and wraps round.  Every row of W
+// starts at a multiple of 2 d bytes, so workgroups that walk k in step ask HBM for the same low
+// address bits at the same time and crowd the same channels; a plain read kernel with this
+// access pattern gets 4.5 TB/s in step and 5.4 to 6.3 TB/s with staggered starts.
 //
 // LDS stages are [rows][4 chunks of 16 B], chunks swizzled as in the 256 x 256 kernel.
 #include <type_traits>
@@ -28,19 +36,22 @@
 namespace fef {
 namespace {
 
-constexpr int SM = 128, SN = 256, SK = 32;
+constexpr int SM = 128, SN = 256, SK = 32;     // SM: rows of the largest tile
 constexpr int kRingW = 8, kRingH = 4;          // stages; loads run kRing - 1 k-steps ahead
 constexpr int kStageW = SN * 4, kStageH = SM * 4;  // 16-byte chunks per stage
-constexpr int kLoadsW = 4, kLoadsH = 2;        // load instructions per loading wavefront per stage
+constexpr int kLoadsW = 4;                     // load instructions per W-loading wavefront per stage
 
+template <int NI>
 struct Frag {
-  bf16x8 a[2][2], b[2][2];  // [16-wide k-slice][32-row / 32-token tile]
+  bf16x8 a[2][NI], b[2][2];  // [16-wide k-slice][32-row / 32-token tile]
 };
 
-template <bool CE>
+// NI = 32-row tiles per wavefront: the workgroup tile has 64 NI rows.
+template <int NI, bool CE>
 __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tiles) {
+  constexpr int kLoadsH = NI;                 // 16 rows per load, 16 NI rows per H-loading wavefront
   __shared__ bf16x8 ringW[kRingW * kStageW];  // 128 KB
-  __shared__ bf16x8 ringH[kRingH * kStageH];  // 32 KB: one workgroup per CU
+  __shared__ bf16x8 ringH[kRingH * kStageH];  // 32 KB (half used when NI = 1): one workgroup per CU
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;  // row half, token column
@@ -51,44 +62,49 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
   const int my_tiles = (n_tiles - (int)blockIdx.x + G - 1) / G;
   const int T = my_tiles * nk;  // steps of this workgroup; even, because nk is
 
-  floatx16 acc[2][2];
+  floatx16 acc[NI][2];
   auto clear_acc = [&]() {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) acc[i][j] = floatx16{};
   };
   clear_acc();
 
   // fragment read addresses inside a stage (chunks); the stage offset is added per step
-  int fa[2][2], fb[2][2];
+  int fa[2][NI], fb[2][2];
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks)
+  for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      fa[ks][i] = swz4(wm * 64 + i * 32 + j32, ks * 2 + h);
-      fb[ks][i] = swz4(wn * 64 + i * 32 + j32, ks * 2 + h);
-    }
-  auto read_frag = [&](int sw, int sh, Frag& f) {
+    for (int i = 0; i < NI; ++i) fa[ks][i] = swz4(wm * (32 * NI) + i * 32 + j32, ks * 2 + h);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) fb[ks][j] = swz4(wn * 64 + j * 32 + j32, ks * 2 + h);
+  }
+  auto read_frag = [&](int sw, int sh, Frag<NI>& f) {
     const bf16x8* As = ringH + sh * kStageH;
     const bf16x8* Bs = ringW + sw * kStageW;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        f.a[ks][i] = As[fa[ks][i]];
-        f.b[ks][i] = Bs[fb[ks][i]];
-      }
+      for (int i = 0; i < NI; ++i) f.a[ks][i] = As[fa[ks][i]];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) f.b[ks][j] = Bs[fb[ks][j]];
+    }
   };
-  auto mfma_row = [&](const Frag& f, int ks, int i) {
+  // The multiplies of one k-slice in two parts: row tile `part` when NI = 2, token tile `part` when NI = 1.
+  auto mfma_part = [&](const Frag<NI>& f, int ks, int part) {
+    if constexpr (NI == 1) {
+      acc[0][part] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ks][0], f.b[ks][part], acc[0][part], 0, 0, 0);
+    } else {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ks][i], f.b[ks][j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 2; ++j)
+        acc[part][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ks][part], f.b[ks][j], acc[part][j], 0, 0, 0);
+    }
   };
 
   // The whole sequence of steps for one loading role.  ROLE 0: this wavefront loads W rows
-  // [64 w, 64 w + 64) of every stage (lead kRingW - 1); ROLE 1: H rows [32 (w - 4), +32) (lead
-  // kRingH - 1).  Lane l of a load owns LDS slot (row + l/4, position l%4) and fetches the chunk
+  // [64 w, 64 w + 64) of every stage (lead kRingW - 1); ROLE 1: H rows [16 NI (w - 4), + 16 NI)
+  // (lead kRingH - 1).  Lane l of a load owns LDS slot (row + l/4, position l%4) and fetches the chunk
   // the swizzle assigns to that slot.  Rows past M / V re-read the last row; they are masked in
   // the epilogue.
   auto run = [&](auto role) {
@@ -102,18 +118,21 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
     int lrow[NL], lchunk[NL];
 #pragma unroll
     for (int n = 0; n < NL; ++n) {
-      lrow[n] = (W_ROLE ? wave * 64 : (wave - 4) * 32) + n * 16 + (lane >> 2);
+      const int r0 = (W_ROLE ? wave * 64 : (wave - 4) * (16 * NI)) + n * 16;
+      lrow[n] = r0 + (lane >> 2);
       lchunk[n] = ((lane & 3) ^ ((lrow[n] >> 2) & 3)) * 8;
-      const bf16x8* base = W_ROLE ? ringW : ringH;
-      slot0[n] = lds_offset(base + ((W_ROLE ? wave * 64 : (wave - 4) * 32) + n * 16) * 4);
+      slot0[n] = lds_offset((W_ROLE ? ringW : ringH) + r0 * 4);
     }
+    // This workgroup's walk over k starts at k-step k0 and wraps round: step t of a tile is
+    // k-step (k0 + t) mod nk, in both roles.
+    const int k0 = (int)((blockIdx.x * 37u) % (unsigned)nk);
     // loader cursor: the next step to load is k-step kl of tile tile_l and goes to stage s_load
     int tile_l = blockIdx.x, kl = 0, s_load = 0, t_load = 0;
-    auto retarget = [&]() {  // gp[] at k = 0 of tile tile_l
+    auto retarget = [&]() {  // gp[] at the first k-step of tile tile_l
 #pragma unroll
       for (int n = 0; n < NL; ++n)
-        gp[n] = W_ROLE ? (const __bf16*)a.W + (size_t)min(tile_l * SN + lrow[n], a.V - 1) * a.d + lchunk[n]
-                       : h_row(a, min(lrow[n], M - 1)) + lchunk[n];
+        gp[n] = (W_ROLE ? (const __bf16*)a.W + (size_t)min(tile_l * SN + lrow[n], a.V - 1) * a.d
+                        : h_row(a, min(lrow[n], M - 1))) + lchunk[n] + k0 * SK;
     };
     retarget();
     auto issue_one = [&](int n) {
@@ -127,6 +146,9 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
         kl = 0;
         tile_l += G;
         if (t_load < T) retarget();
+      } else if (kl == nk - k0) {  // back to k = 0
+#pragma unroll
+        for (int n = 0; n < NL; ++n) gp[n] -= a.d;
       }
     };
     auto wait_ahead = [&](int stages) {  // at most `stages` younger stages may stay in flight
@@ -153,7 +175,7 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
     }
     wait_ahead(npro - 1);  // own loads of stage 0 have landed
     lds_barrier();
-    Frag f0, f1;
+    Frag<NI> f0, f1;
     read_frag(0, 0, f0);
     int sw = 0, sh = 0;               // stages of the current step in the two rings
     int tile_c = blockIdx.x, kc = 0;  // compute cursor
@@ -163,7 +185,7 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
     };
     auto end_of_step = [&]() {  // tile finished: epilogue from the registers, next tile starts at zero
       if (++kc == nk) {
-        store_logits_and_partials<2, CE>(a, acc, wm * 64, tile_c * SN + wn * 64, M, lane);
+        store_logits_and_partials<NI, CE>(a, acc, wm * (32 * NI), tile_c * SN + wn * 64, M, lane);
         clear_acc();
         kc = 0;
         tile_c += G;
@@ -175,28 +197,28 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
     // publishes that stage and tells that everybody has left stage t-1, which is refilled with
     // step t+LEAD between the multiplies.  The fragment reads of the next stage sit in the middle
     // of the multiplies.
-    auto step_steady = [&](const Frag& cur, Frag& nxt) {
+    auto step_steady = [&](const Frag<NI>& cur, Frag<NI>& nxt) {
       __builtin_amdgcn_sched_barrier(0);
       wait_newer<(LEAD - 2) * NL>();
       lds_barrier();
       next_stage();
-      mfma_row(cur, 0, 0);
+      mfma_part(cur, 0, 0);
       issue_one(0);
-      mfma_row(cur, 0, 1);
-      issue_one(1);
+      mfma_part(cur, 0, 1);
+      if constexpr (NL > 1) issue_one(1);
       __builtin_amdgcn_sched_barrier(0);
       read_frag(sw, sh, nxt);
       __builtin_amdgcn_sched_barrier(0);
-      mfma_row(cur, 1, 0);
+      mfma_part(cur, 1, 0);
       if constexpr (NL > 2) issue_one(2);
-      mfma_row(cur, 1, 1);
+      mfma_part(cur, 1, 1);
       if constexpr (NL > 3) issue_one(3);
       __builtin_amdgcn_sched_barrier(0);
       loaded_step();
       end_of_step();
     };
     // General step for the end of the sequence: refills only while steps are left, waits by count.
-    auto step_tail = [&](int t, const Frag& cur, Frag& nxt) {
+    auto step_tail = [&](int t, const Frag<NI>& cur, Frag<NI>& nxt) {
       wait_ahead(min(t + LEAD - 1, T - 1) - t - 1);
       lds_barrier();
       next_stage();
@@ -209,7 +231,7 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) mfma_row(cur, ks, i);
+        for (int part = 0; part < 2; ++part) mfma_part(cur, ks, part);
       end_of_step();
     };
     int t = 0;
@@ -230,6 +252,12 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
 
 bool stream_supports(int M, int d) { return M <= SM && d % 64 == 0; }
 
+template <int NI>
+static void launch_stream(const HeadArgs& a, int grid, int n_tiles) {
+  if (a.labels) FEF_LAUNCH_HEAD((head_stream_kernel<NI, true>), dim3((unsigned)grid), dim3(512), a, a, n_tiles);
+  else FEF_LAUNCH_HEAD((head_stream_kernel<NI, false>), dim3((unsigned)grid), dim3(512), a, a, n_tiles);
+}
+
 hipError_t launch_head_stream(const HeadArgs& a) {
   const int n_tiles = (a.V + SN - 1) / SN;
   // one workgroup per CU (the kernel uses all of a CU's LDS); each walks its tiles back to back
@@ -245,8 +273,8 @@ hipError_t launch_head_stream(const HeadArgs& a) {
     cus[dev] = n > 0 ? n : 1;
   }
   const int grid = n_tiles < cus[dev] ? n_tiles : cus[dev];
-  if (a.labels) FEF_LAUNCH_HEAD(head_stream_kernel<true>, dim3((unsigned)grid), dim3(512), a, a, n_tiles);
-  else FEF_LAUNCH_HEAD(head_stream_kernel<false>, dim3((unsigned)grid), dim3(512), a, a, n_tiles);
+  if (a.nrows <= 64) launch_stream<1>(a, grid, n_tiles);
+  else launch_stream<2>(a, grid, n_tiles);
   return hipGetLastError();
 }
 
