@@ -137,25 +137,28 @@ def test_tiled256_kernel_small_shapes(B, K, d, V):
 
 
 @pytest.mark.parametrize("B,K,d,V", [(5, 8, 64, 1000), (3, 5, 128, 777), (8, 8, 512, 2050), (1, 1, 64, 1),
-                                     (4, 16, 256, 300), (2, 9, 3584, 1500), (6, 8, 1024, 513), (7, 8, 512, 2049)])
+                                     (4, 16, 256, 300), (2, 9, 3584, 1500), (6, 8, 1024, 513), (7, 8, 512, 2049),
+                                     (4, 8, 256, 600), (3, 11, 128, 520)])
 def test_stream_kernel_small_shapes(B, K, d, V):
-    """All rows x 256 tokens per workgroup, k halves added through LDS: 2 to 128 rows through the
-    head, k loops of 2 to 112 steps (prologue only, tail only, steady groups plus tail), ragged V."""
+    """Persistent workgroups of 64 rows (M <= 64) or 128 rows x 256 tokens: 2 to 128 rows through the
+    head including M = 64 and 66 on either side of the switch, k loops of 2 to 112 steps (prologue only,
+    tail only, steady steps plus tail) each started at another k-step and wrapped, ragged V."""
     ref, out, st = run_case(B, K, max(K, 16), d, V, seed=16, rho=0.8, variant=fb.FEF_GEMM_STREAM)
     assert st["near_flipped"] <= B // 20
 
 
-def test_llada_shape_batch8_through_the_streaming_kernel(llada_head):
-    """B=8 at full d and V (128 rows through the head): the configuration AUTO gives the streaming
-    kernel; the oracle checks a seeded subset of sequences."""
+@pytest.mark.parametrize("B", [4, 8])
+def test_llada_shape_through_the_streaming_kernel(llada_head, B):
+    """B=4 and B=8 at full d and V (64 and 128 rows through the head, the two tile heights): the
+    configurations AUTO gives the streaming kernel; the oracle checks a seeded subset of sequences."""
     wl, W, Wd, W64 = llada_head
-    B, K, block = 8, 8, 32
+    K, block = 8, 32
     vs = fb.VerifyStep(B, K, block, wl.d, wl.V, device=DEV, diag=True)
     assert fb.fef_select_gemm(vs._params(), K) == fb.FEF_GEMM_STREAM
     hd, ht = synth.make_hidden(B, K, wl.d, 9, wl.rho, wl.sigma_h, "bf16", 0, 2)
     tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 9, step=2)
     torch.cuda.synchronize()
-    for b in [0, 3, 7]:
+    for b in [0, 3, B - 1]:
         r = O.verify_step(synth.to_f64(hd[b:b + 1]), synth.to_f64(ht[b:b + 1]), W64, K, block, 9, step=2,
                           seq_base=b)
         diag = {k: _np(v)[b:b + 1] if k != "lse" else _np(v)[:, b:b + 1] for k, v in vs.diag.items()}
