@@ -246,6 +246,27 @@ def main():
     head_ms = [ev.elapsed_ms(a, b) for a, b in pairs[:args.steps]]
     head_avg_s = sum(head_ms) / len(head_ms) / 1e3
 
+    # Outside the timed region: positions committed by the same steps (the decisions are a function
+    # of inputs and seed, so a second pass repeats them), and the rate of a plain read of W.
+    committed = 0
+    if not args.split:
+        counts = []
+        for i in range(args.steps):
+            hd, ht = rounds_d[i % n_rounds]
+            tok, _, _ = vs(hd, ht, Wd, args.seed, step=i, temperature=wl.temperature)
+            counts.append((tok >= 0).sum())
+        committed = int(torch.stack(counts).sum().item())
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        fb.fef_read_probe(Wd, sink)
+    e0.record()
+    for _ in range(10):
+        fb.fef_read_probe(Wd, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    read_ceiling = Wd.numel() * Wd.element_size() * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
     ms_per_step = elapsed / args.steps * 1e3
     positions = wl.B * wl.K
     M = positions if args.split else 2 * positions   # rows through one head launch
@@ -266,7 +287,10 @@ def main():
                             fb.FEF_GEMM_STREAM: "head_stream_kernel",
                             fb.FEF_GEMM_F32: "head_f32_kernel"}[variant],
                  "avg_kernel_us": head_avg_s * 1e6, "algorithmic_bytes": hb, "flops": flops,
-                 "events": "separate" if args.graph else args.events})
+                 "events": "separate" if args.graph else args.events,
+                 "plain_read_of_W_GBs": read_ceiling})
+    if roof["bound"] == "hbm":
+        roof["frac_of_plain_read"] = roof["achieved"] / read_ceiling
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
@@ -280,6 +304,7 @@ def main():
         "unit": "positions/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "committed_positions_per_s": committed / elapsed if committed else None,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "K": wl.K, "block": wl.block, "d": wl.d, "V": wl.V,

@@ -54,7 +54,7 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 7
+#define FEF_ABI_VERSION 8
 
 typedef enum {
   FEF_OK = 0,
@@ -226,6 +226,13 @@ float fef_uniform(uint64_t seed, uint32_t position, uint32_t step, uint32_t sequ
  * traffic (nbytes read + nbytes written).  Profiler byte counters are scaled by what they
  * report for this kernel.  Asynchronous on `stream` (hipStream_t, NULL = null stream). */
 fef_status fef_copy_probe(void* dst, const void* src, size_t nbytes, void* stream);
+
+/* Measurement aid, not part of the verify path: read nbytes (a multiple of 16) at src (device,
+ * 16-byte aligned) once, contiguously, with nothing else to do: the streaming-read rate this
+ * gives is the practical ceiling the HBM-bound head kernels are compared with.  `sink` (device,
+ * 4 bytes, caller-owned) exists so that the reads have a use; it is written only if the XOR of
+ * all words equals one particular value.  Asynchronous on `stream`. */
+fef_status fef_read_probe(const void* src, size_t nbytes, void* sink, void* stream);
 
 const char* fef_status_string(fef_status s);
 const char* fef_last_error(void);

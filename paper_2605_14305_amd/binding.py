@@ -20,10 +20,10 @@ FEF_GEMM_AUTO, FEF_GEMM_SKINNY, FEF_GEMM_TILED, FEF_GEMM_F32, FEF_GEMM_TILED256,
 FEF_MAX_K, FEF_MAX_BLOCK = 64, 4096
 FEF_PHASE_FUSED, FEF_PHASE_DRAFT, FEF_PHASE_TARGET = 0, 1, 2
 
-ABI_VERSION = 7   # FEF_ABI_VERSION of include/fef.h this binding's fef_params mirrors
+ABI_VERSION = 8   # FEF_ABI_VERSION of include/fef.h this binding's fef_params mirrors
 
 EXPORTS = ["fef_workspace_bytes", "fef_verify_step", "fef_select_gemm", "fef_uniform",
-           "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe",
+           "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe", "fef_read_probe",
            "fef_cross_entropy_workspace_bytes", "fef_head_cross_entropy", "fef_topn_step"]
 
 
@@ -85,6 +85,8 @@ def lib():
         L.fef_last_error.argtypes = []
         L.fef_copy_probe.restype = ctypes.c_int
         L.fef_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.fef_read_probe.restype = ctypes.c_int
+        L.fef_read_probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
         L.fef_abi_version.restype = ctypes.c_int32
         L.fef_abi_version.argtypes = []
         L.fef_cross_entropy_workspace_bytes.restype = ctypes.c_size_t
@@ -150,6 +152,14 @@ def fef_copy_probe(dst, src):
     """Plain device copy of known traffic (profiler counter calibration)."""
     assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
     s = lib().fef_copy_probe(_ptr(dst), _ptr(src), src.numel() * src.element_size(),
+                             ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    if s != FEF_OK:
+        raise FefError(s, fef_last_error())
+
+
+def fef_read_probe(src, sink):
+    """Plain streaming read of `src` (the practical HBM read ceiling); `sink` is a 4-byte device tensor."""
+    s = lib().fef_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
                              ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     if s != FEF_OK:
         raise FefError(s, fef_last_error())

@@ -134,9 +134,40 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(uint4* __restrict__ dst
     dst[i] = src[i];
 }
 
+// Each workgroup reads one contiguous share, eight 16-byte loads per thread in flight.
+__global__ __launch_bounds__(256) void read_probe_kernel(const uint4* __restrict__ src, size_t n16, unsigned* sink) {
+  constexpr int U = 8;
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t begin = blockIdx.x * per, end = begin + per < n16 ? begin + per : n16;
+  uint4 acc = {0u, 0u, 0u, 0u};
+  for (size_t i = begin + threadIdx.x; i < end; i += 256 * U) {
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t j = i + (size_t)u * 256;
+      v[u] = j < end ? src[j] : uint4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w;
+    }
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) *sink = 1u;
+}
+
 }  // namespace
 
 extern "C" {
+
+fef_status fef_read_probe(const void* src, size_t nbytes, void* sink, void* stream) {
+  if (!src || !sink || nbytes == 0 || nbytes % 16 || ((uintptr_t)src & 15) || ((uintptr_t)sink & 3))
+    return fail(FEF_ERR_INVALID_ARG, "read probe needs a non-NULL 16-byte aligned source, a size multiple of 16 and a sink");
+  hipLaunchKernelGGL(read_probe_kernel, dim3(2048), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+                     nbytes / 16, (unsigned*)sink);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FEF_ERR_HIP, "read probe launch: %s", hipGetErrorString(e));
+  return FEF_OK;
+}
 
 fef_status fef_copy_probe(void* dst, const void* src, size_t nbytes, void* stream) {
   if (!dst || !src || nbytes == 0 || nbytes % 16 || (((uintptr_t)dst | (uintptr_t)src) & 15))
