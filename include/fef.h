@@ -89,7 +89,9 @@ typedef enum {
  * must follow a DRAFT call with the same sizes, mask_in, seed, step and the SAME workspace,
  * left untouched in between (it holds the draft logits, their log-sum-exp and x~); h_draft is
  * not read and may be NULL.  DRAFT + TARGET give bit-identical results to FUSED when both
- * use the same head kernel, and read W twice. */
+ * use the same head kernel, and read W twice.  The two calls may pass different W_vocab of the
+ * same shape: a separate draft model with its own output embedding (the "A / B" rows of the
+ * ablation on the choice of draft model). */
 typedef enum { FEF_PHASE_FUSED = 0, FEF_PHASE_DRAFT = 1, FEF_PHASE_TARGET = 2 } fef_phase;
 
 typedef struct {

@@ -177,7 +177,7 @@ def recorrupt(selected, prob, seed, pos_base, step, sequence):
 def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0,
                 seq_base=0, pos_base=0, n_rm=-1, final_pass=False, lowconf_scope=0,
                 mask_in=None, pass_mask=None, conf=None, draft_tokens=None,
-                return_logits=False, recorrupt_prob=1.0, greedy=False):
+                return_logits=False, recorrupt_prob=1.0, greedy=False, W_draft=None):
     """One speculative round for B sequences.
 
     h_draft, h_target: [B,K,d] float64 (row m belongs to window slot m); W: [V,d] float64.
@@ -200,10 +200,15 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
         commits argmax p and is counted in resid_fallbacks.
       * greedy=True: the zero-temperature limit described in the module header; `temperature`
         then only scales the logits the confidences are taken from.
+      * W_draft: output embedding of a separate draft model ("A / B" of the ablation on the choice
+        of draft model, Ablation 3 and Table 4): the draft laws are softmax(h_draft W_draft^T / tau), the target
+        laws keep W.  None = one model for both, the paper's default.
     """
     h_draft = np.asarray(h_draft, dtype=np.float64)
     h_target = np.asarray(h_target, dtype=np.float64)
     W = np.asarray(W, dtype=np.float64)
+    W_q = W if W_draft is None else np.asarray(W_draft, dtype=np.float64)
+    assert W_q.shape == W.shape
     B, Kh, d = h_draft.shape
     V = W.shape[0]
     assert Kh == K and h_target.shape == h_draft.shape and W.shape[1] == d
@@ -234,7 +239,7 @@ def verify_step(h_draft, h_target, W, K, block, seed, *, temperature=1.0, step=0
     for m in range(K):
         active = m < window
         # S2 / S4: the two laws of slot m
-        Lq = head_logits(h_draft[:, m, :], W, temperature)
+        Lq = head_logits(h_draft[:, m, :], W_q, temperature)
         Lp = head_logits(h_target[:, m, :], W, temperature)
         q, lse_q = law(Lq)
         p, lse_p = law(Lp)

@@ -540,6 +540,26 @@ def test_acceptance_sweep_matches_theorem_2(llada_head):
     assert min(alphas_seen) < 0.35 and max(alphas_seen) > 0.8     # the sweep spans low and high acceptance
 
 
+@pytest.mark.parametrize("B,K,d,V", [(1, 8, 512, 3000), (6, 8, 256, 2050), (40, 4, 128, 700)])
+def test_separate_draft_model_head(B, K, d, V):
+    """Ablation 3's "A / B" setting: the DRAFT call projects with the draft model's own output
+    embedding, the TARGET call with the verify model's.  Oracle: the same round with W_draft."""
+    block = 16
+    W_t = synth.make_head(V, d, 21)
+    W_d = (0.8 * W_t.float() + 0.6 * synth.make_head(V, d, 22).float()).to(torch.bfloat16)
+    hd, ht = synth.make_hidden(B, K, d, 21, 0.8, 3.0 / (0.02 * np.sqrt(d)))
+    vs = fb.VerifyStep(B, K, block, d, V, device=DEV, diag=True, diag_logits=True)
+    tok, _, _ = vs(hd.to(DEV), None, W_d.to(DEV), 21, step=2, phase=fb.FEF_PHASE_DRAFT)
+    tok, acc, rem = vs(None, ht.to(DEV), W_t.to(DEV), 21, step=2, phase=fb.FEF_PHASE_TARGET)
+    torch.cuda.synchronize()
+    ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), synth.to_f64(W_t), K, block, 21, step=2,
+                        return_logits=True, W_draft=synth.to_f64(W_d))
+    shared = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), synth.to_f64(W_t), K, block, 21, step=2)
+    assert not np.array_equal(ref.draft_tokens, shared.draft_tokens)    # the second head matters
+    st = parity.compare(ref, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs.diag.items()})
+    assert st["near_flipped"] <= B // 20
+
+
 @pytest.mark.parametrize("B,K,d,V,variant", [(1, 8, 512, 3000, fb.FEF_GEMM_AUTO), (2, 8, 512, 3000, fb.FEF_GEMM_AUTO),
                                               (6, 4, 128, 1000, fb.FEF_GEMM_TILED), (40, 4, 64, 700, fb.FEF_GEMM_TILED256)])
 def test_split_draft_then_target_call_order(B, K, d, V, variant):
