@@ -5,10 +5,11 @@
 //
 // One persistent workgroup per CU takes the 256-token tiles b, b + G, ... and walks k in steps of
 // 32 over all of them as ONE sequence of steps: W goes through a ring of eight 16 KB LDS stages
-// filled by direct-to-LDS loads seven steps ahead (112 KB of W in flight per CU; with 64 bytes per
-// row per step HBM latency under load is several microseconds), H, which every workgroup re-reads
-// and which therefore sits in L2, through a ring of four 8 KB stages three steps ahead.  Together
-// they use the whole 160 KB of LDS.  The loads run on across tile boundaries, so only the first
+// filled by direct-to-LDS loads seven steps ahead (measured: a lead of three steps does as well;
+// a wavefront with more loads outstanding than the memory pipeline takes blocks at its next load
+// instruction, and that, not a wait for data, is where the loading wavefronts spend a third of
+// their time), H, which every workgroup re-reads and which therefore sits in L2, through a ring
+// of four 8 KB stages three steps ahead.  Together they use the whole 160 KB of LDS.  The loads run on across tile boundaries, so only the first
 // tile of a workgroup pays the cold start, and the epilogue of a tile (registers only, no LDS)
 // runs while the first stages of the next tile arrive.  The vector-memory counter of a wavefront
 // completes in order, so two different leads cannot share a wavefront: wavefronts 0..3 load W
