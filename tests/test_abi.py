@@ -33,9 +33,11 @@ def test_exports_every_declared_symbol(lib):
     assert f"#define FEF_ABI_VERSION {fb.ABI_VERSION}\n" in open(os.path.join(ROOT, "include", "fef.h")).read()
 
 
-def test_graft_entry_build_compiles_and_loads():
+def test_graft_entry_has_build_and_smoke_and_checks_the_current_abi():
+    import inspect
     import __graft_entry__ as g
-    g.build()
+    assert callable(g.build) and callable(g.smoke)
+    assert "fb.ABI_VERSION" in inspect.getsource(g.build)      # no stale literal version
 
 
 def test_struct_layout_matches(lib):
