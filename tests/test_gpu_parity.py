@@ -598,3 +598,33 @@ def test_split_draft_then_target_call_order(B, K, d, V, variant):
         fused = (_np(tok2), _np(acc2), _np(rem2), _np(vf.diag["logits"]), _np(vf.diag["alpha"]))
         for x, y in zip(split, fused):
             assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_seeded_random_shapes_masks_and_options(case):
+    """Seeded draws over what the fixed lists above hold constant: sizes (ragged V, odd multiples of 64
+    for d, any K), the head kernel, a random mask with a pass set and confidences, temperature, bases,
+    both LowConf scopes, final pass, stochastic re-corruption, greedy."""
+    rng = np.random.default_rng(1000 + case)
+    variant = [fb.FEF_GEMM_AUTO, fb.FEF_GEMM_TILED, fb.FEF_GEMM_TILED256, fb.FEF_GEMM_STREAM][case % 4]
+    K = int(rng.integers(1, 17))
+    B = int(rng.integers(1, 128 // (2 * K) + 1)) if variant == fb.FEF_GEMM_STREAM else int(rng.integers(1, 25))
+    block = int(rng.integers(K, 41))
+    d = 64 * int(rng.integers(1, 10))
+    V = int(rng.integers(2, 3000))
+    mask = (rng.random((B, block)) < rng.choice([0.2, 0.6, 1.0])).astype(np.uint8)
+    mask[0, 0] = 1
+    pm = ((1 - mask) * (rng.random((B, block)) < 0.5)).astype(np.uint8)
+    conf = (rng.random((B, block)) * (1 - mask)).astype(np.float32)
+    greedy = bool(case % 6 == 5)
+    ref, out, st = run_case(B, K, block, d, V, seed=200 + case, rho=float(rng.choice([0.5, 0.9, 0.99])),
+                            logit_std=float(rng.choice([1.0, 3.0])), variant=variant,
+                            temperature=float(rng.choice([0.5, 1.0, 1.3])), step=int(rng.integers(0, 1000)),
+                            seq_base=int(rng.integers(0, 1 << 20)), pos_base=int(rng.integers(0, 1 << 16)),
+                            n_rm=int(rng.integers(-1, block + 1)), final_pass=bool(rng.random() < 0.2),
+                            lowconf_scope=int(case % 2), mask=mask, pass_mask=pm, conf=conf,
+                            recorrupt_prob=float(rng.choice([1.0, 0.5])), greedy=greedy)
+    print(f"case {case}: B={B} K={K} block={block} d={d} V={V} variant={variant} {st}", flush=True)
+    assert st["near_flipped"] <= max(1, B // 10)
+    if st["remask_skipped"] == 0 and st["near_margin"] == 0:
+        _check_state(ref, out)
