@@ -281,19 +281,36 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
   float mass[PER > 0 ? PER : 1];  // exp-sums of this lane's tiles relative to the row maximum
   float mx = -INFINITY, sm = 0.f;
   if constexpr (PER > 0) {
+    // Lane l owns the consecutive tiles l*PER .. l*PER + PER-1 (the ordered search below needs
+    // that).  With few partials per lane it loads them as they lie (PER * 8 contiguous bytes per
+    // lane); with many it loads tile j*64 + l, 512 contiguous bytes per instruction, and hands
+    // each exp-sum to its owner through this wavefront's slice of LDS (rows of PER + 1 floats,
+    // an odd stride, so both directions are conflict-free).
+    constexpr bool EXCHANGE = PER > 8;
+    __shared__ float exchange[EXCHANGE ? NW : 1][EXCHANGE ? kWave * (PER + 1) : 1];
     float2 p[PER];
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-      const int t = lane * PER + j;
+      const int t = EXCHANGE ? j * kWave + lane : lane * PER + j;
       p[j] = t < a.nT ? P[t] : make_float2(-INFINITY, 0.f);
       mx = fmaxf(mx, p[j].x);
     }
     mx = wave_max(mx);
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-      mass[j] = p[j].y > 0.f ? p[j].y * expf(p[j].x - mx) : 0.f;
-      sm += mass[j];
+    for (int j = 0; j < PER; ++j) mass[j] = p[j].y > 0.f ? p[j].y * expf(p[j].x - mx) : 0.f;
+    if constexpr (EXCHANGE) {
+      float* ex = exchange[wave];
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        const int t = j * kWave + lane;
+        ex[(t / PER) * (PER + 1) + t % PER] = mass[j];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");  // same wavefront on both sides: order only
+#pragma unroll
+      for (int j = 0; j < PER; ++j) mass[j] = ex[lane * (PER + 1) + j];
     }
+#pragma unroll
+    for (int j = 0; j < PER; ++j) sm += mass[j];
   } else {
     for (int t = lane; t < a.nT; t += kWave) mx = fmaxf(mx, P[t].x);
     mx = wave_max(mx);
