@@ -25,5 +25,21 @@ def build(verbose=True, extra_flags=()):
     return LIB
 
 
+HARNESS_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "abi_harness.cpp")
+HARNESS = os.path.join(HERE, "abi_harness")
+
+
+def build_harness(verbose=True):
+    """The C++ program that calls libfef.so through include/fef.h alone (run by the GPU tests)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-std=c++17", "-O1", "-Wall", "-I", os.path.join(os.path.dirname(HERE), "include"), HARNESS_SRC,
+           "-L", HERE, "-lfef", "-Wl,-rpath,$ORIGIN", "-o", HARNESS]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return HARNESS
+
+
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:])
+    build_harness()
