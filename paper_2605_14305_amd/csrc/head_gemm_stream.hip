@@ -30,6 +30,7 @@
 // access pattern gets 4.5 TB/s in step and 5.4 to 6.3 TB/s with staggered starts.
 //
 // LDS stages are [rows][4 chunks of 16 B], chunks swizzled as in the 256 x 256 kernel.
+#include <atomic>
 #include <type_traits>
 
 #include "head_common.hpp"
@@ -262,18 +263,20 @@ static void launch_stream(const HeadArgs& a, int grid, int n_tiles) {
 hipError_t launch_head_stream(const HeadArgs& a) {
   const int n_tiles = (a.V + SN - 1) / SN;
   // one workgroup per CU (the kernel uses all of a CU's LDS); each walks its tiles back to back
-  static int cus[64];
+  static std::atomic<int> cus[64];  // CU count per device, 0 = not asked yet; callers may be concurrent threads
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (cus[dev] == 0) {
+  int n_cu = cus[dev].load(std::memory_order_relaxed);
+  if (n_cu == 0) {
     int n = 0;
     e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
-    cus[dev] = n > 0 ? n : 1;
+    n_cu = n > 0 ? n : 1;
+    cus[dev].store(n_cu, std::memory_order_relaxed);
   }
-  const int grid = n_tiles < cus[dev] ? n_tiles : cus[dev];
+  const int grid = n_tiles < n_cu ? n_tiles : n_cu;
   if (a.nrows <= 64) launch_stream<1>(a, grid, n_tiles);
   else launch_stream<2>(a, grid, n_tiles);
   return hipGetLastError();
