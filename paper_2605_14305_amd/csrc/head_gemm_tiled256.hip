@@ -175,6 +175,24 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
   else if (1 < nk) wait_newer<2 * QI>();
   else wait_newer<0>();
   lds_barrier();
+  if (m0 + wm * 128 >= M) {
+    // None of this wavefront's 128 rows exists (the last row tile of a launch whose M is no
+    // multiple of 256): it keeps its share of the loads and every barrier, in the order of the
+    // steps below, and multiplies nothing.
+    auto idle_step = [&](bf16x8* refill, int kt) {
+      if (kt + 2 < nk) wait_newer<2 * QI>();
+      else wait_newer<0>();
+      lds_barrier();
+      if (kt + 3 < nk) issue(refill, kt + 3);
+    };
+    for (int kt = 0; kt < nk; kt += 4) {
+      idle_step(st3, kt);
+      if (kt + 1 < nk) idle_step(st0, kt + 1);
+      if (kt + 2 < nk) idle_step(st1, kt + 2);
+      if (kt + 3 < nk) idle_step(st2, kt + 3);
+    }
+    return;
+  }
   read_frag(st0, 0, cur);
   int kt = 0;
   if (6 < nk) {  // the steady loop refills k-step kt + 3: point the loads there
