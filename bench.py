@@ -84,6 +84,45 @@ def cpu_baseline(wl, W, rounds, seed, budget_s=20.0):
                       f"numpy fp64, {el:.1f} s; host has {len(os.sched_getaffinity(0))} usable cores"}
 
 
+def acceptance_sweep(args, wl, Wd, dev):
+    """The acceptance-rate sweep of the batched configuration: for draft/target correlations rho and
+    temperatures tau, `--sweep N` calls each; reports the mean overlap alpha = sum min(p, q) the calls
+    return, the mean committed length they produce, the closed form (1 - alpha^K) / (1 - alpha) of
+    Theorem 2 at that mean alpha, and the idealised acceleration S = E[C] / 2 (Corollary 2)."""
+    import torch
+    from paper_2605_14305_amd import binding as fb
+    from paper_2605_14305_amd import synth
+    vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, dtype=wl.dtype, device=dev, diag=True)
+    rows = []
+    for rho in (0.5, 0.9, 0.99):
+        batches = [tuple(t.to(dev) for t in synth.make_hidden(wl.B, wl.K, wl.d, args.seed, rho, wl.sigma_h, wl.dtype, 0, r))
+                   for r in range(8)]
+        for tau in (0.5, 1.0):
+            alpha_sum = torch.zeros((), dtype=torch.float64, device=dev)
+            committed = torch.zeros((), dtype=torch.float64, device=dev)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.sweep):
+                hd, ht = batches[i % len(batches)]
+                tok, acc, _ = vs(hd, ht, Wd, args.seed, step=i, temperature=tau)
+                alpha_sum += vs.diag["alpha"].double().mean()
+                committed += torch.clamp(acc + 1, max=wl.K).double().mean()
+            torch.cuda.synchronize()
+            el = time.perf_counter() - t0
+            a = float(alpha_sum.item()) / args.sweep
+            ec = wl.K if a >= 1.0 else (1.0 - a ** wl.K) / (1.0 - a)
+            rows.append({"rho": rho, "tau": tau, "calls": args.sweep, "mean_alpha": a,
+                         "mean_committed": float(committed.item()) / args.sweep,
+                         "theorem2_at_mean_alpha": ec, "S_ideal": ec / 2.0, "us_per_call": el / args.sweep * 1e6})
+            print("rho %.2f tau %.1f: alpha %.3f  committed %.3f  (1-a^K)/(1-a) %.3f  S %.2f  %.0f us/call"
+                  % (rho, tau, a, rows[-1]["mean_committed"], ec, ec / 2, rows[-1]["us_per_call"]), file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "acceptance sweep of the verify step (mean overlap, committed length, Theorem 2)",
+                      "n_gpus": 1, "data": "synthetic", "dtype": wl.dtype,
+                      "config": {"workload": wl.name, "B": wl.B, "K": wl.K, "block": wl.block, "d": wl.d, "V": wl.V,
+                                 "logit_std": wl.logit_std, "diagnostics": "alpha of every slot"},
+                      "rows": rows}), flush=True)
+
+
 def bench_cross_entropy(args, wl, W, Wd, dev):
     """One step = one fef_head_cross_entropy call on R rows (head kernel without logits store,
     per-row log-sum-exp merge, loss sum)."""
@@ -163,6 +202,9 @@ def main():
     ap.add_argument("--ce", type=int, default=0, metavar="R",
                     help="instead of the verify step, time the cross-entropy use of the head (Algorithm 1's "
                          "token-level loss, forward only) on R rows of the workload's head shape")
+    ap.add_argument("--sweep", type=int, default=0, metavar="N",
+                    help="instead of the timed step, run the acceptance sweep (rho x tau, N calls each) on the "
+                         "workload's shape and print its table as one JSON line")
     ap.add_argument("--events", choices=["inline", "separate"], default="inline",
                     help="record the head-kernel events inside the timed steps, or in a second pass")
     ap.add_argument("--event-every", type=int, default=4, metavar="N",
@@ -193,6 +235,8 @@ def main():
     Wd = W.to(dev)
     if args.ce:
         return bench_cross_entropy(args, wl, W, Wd, dev)
+    if args.sweep:
+        return acceptance_sweep(args, wl, Wd, dev)
     n_rounds = 16   # distinct hidden-state batches, cycled, so only W could ever sit in a cache
     rounds = [synth.make_round(wl, args.seed, block_index=i // 8, step=i) for i in range(n_rounds)]
     rounds_d = [(hd.to(dev), ht.to(dev)) for hd, ht in rounds]
