@@ -54,7 +54,8 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 8
+#define FEF_ABI_VERSION 9
+#define FEF_STATIC_SCRATCH_BYTES (32u << 20) /* built-in scratch of fef_verify_step_static        */
 
 typedef enum {
   FEF_OK = 0,
@@ -175,6 +176,22 @@ size_t fef_workspace_bytes(const fef_params* prm, int32_t K, int32_t block);
 fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const void* h_target,
                            const void* W_vocab, int32_t K, int32_t block, uint64_t seed,
                            int32_t* out_tokens, int32_t* out_accept_len, uint8_t* out_remask);
+
+/* fef_verify_step for callers that cannot allocate device memory and have no workspace to hand
+ * over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as fef_verify_step (all three phases), except that
+ * prm->workspace and prm->workspace_bytes are ignored: the scratch is a buffer of
+ * FEF_STATIC_SCRATCH_BYTES (32 MiB) built into the library, one copy per GPU, held until the
+ * process ends.  The call allocates nothing.  A call whose fef_workspace_bytes exceeds that size
+ * (at V = 126464: more than 64 rows through the head, 2*B*K fused) returns FEF_ERR_WORKSPACE and
+ * enqueues nothing.  The buffer keeps the previous call's contents; nothing in it has to start at
+ * zero (every word is written before it is read within a call), and a TARGET call finds what the
+ * DRAFT call before it left there.  All calls on one GPU share the buffer: calls that overlap in
+ * time on one GPU (different streams or threads) race, so order them.  The first call on a device
+ * looks the buffer's address up (with that device current); make it outside graph capture. */
+fef_status fef_verify_step_static(const fef_params* prm, const void* h_draft, const void* h_target,
+                                  const void* W_vocab, int32_t K, int32_t block, uint64_t seed,
+                                  int32_t* out_tokens, int32_t* out_accept_len, uint8_t* out_remask);
 
 /* The decoding step the paper's speed-ups are measured against (Main Results: LLaDA decodes one
  * token per step, the LLaDA/2 variant two): every window position gets its law from ONE forward,

@@ -20,11 +20,13 @@ FEF_GEMM_AUTO, FEF_GEMM_SKINNY, FEF_GEMM_TILED, FEF_GEMM_F32, FEF_GEMM_TILED256,
 FEF_MAX_K, FEF_MAX_BLOCK = 64, 4096
 FEF_PHASE_FUSED, FEF_PHASE_DRAFT, FEF_PHASE_TARGET = 0, 1, 2
 
-ABI_VERSION = 8   # FEF_ABI_VERSION of include/fef.h this binding's fef_params mirrors
+ABI_VERSION = 9   # FEF_ABI_VERSION of include/fef.h this binding's fef_params mirrors
 
 EXPORTS = ["fef_workspace_bytes", "fef_verify_step", "fef_select_gemm", "fef_uniform",
            "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe", "fef_read_probe",
-           "fef_cross_entropy_workspace_bytes", "fef_head_cross_entropy", "fef_topn_step"]
+           "fef_cross_entropy_workspace_bytes", "fef_head_cross_entropy", "fef_topn_step",
+           "fef_verify_step_static"]
+FEF_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class fef_params(ctypes.Structure):
@@ -74,6 +76,8 @@ def lib():
         L.fef_verify_step.argtypes = [ctypes.POINTER(fef_params), ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.fef_verify_step_static.restype = ctypes.c_int
+        L.fef_verify_step_static.argtypes = L.fef_verify_step.argtypes
         L.fef_select_gemm.restype = ctypes.c_int32
         L.fef_select_gemm.argtypes = [ctypes.POINTER(fef_params), ctypes.c_int32]
         L.fef_uniform.restype = ctypes.c_float
@@ -143,6 +147,17 @@ def fef_verify_step(params, h_draft, h_target, W_vocab, K, block, seed, out_toke
     s = lib().fef_verify_step(ctypes.byref(params), _ptr(h_draft), _ptr(h_target), _ptr(W_vocab), K,
                               block, ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), _ptr(out_tokens),
                               _ptr(out_accept_len), _ptr(out_remask))
+    if s != FEF_OK:
+        raise FefError(s, fef_last_error())
+    return s
+
+
+def fef_verify_step_static(params, h_draft, h_target, W_vocab, K, block, seed, out_tokens, out_accept_len,
+                           out_remask):
+    """fef_verify_step on the library's built-in scratch buffer: no workspace, no allocation."""
+    s = lib().fef_verify_step_static(ctypes.byref(params), _ptr(h_draft), _ptr(h_target), _ptr(W_vocab), K,
+                                     block, ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), _ptr(out_tokens),
+                                     _ptr(out_accept_len), _ptr(out_remask))
     if s != FEF_OK:
         raise FefError(s, fef_last_error())
     return s

@@ -4,8 +4,15 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "../../include/fef.h"
 #include "fef_device.hpp"
+
+// Scratch of fef_verify_step_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; the device address it
+// yields (one per device) is what kernels, memsets and copies must be given.
+static __device__ __align__(256) unsigned char scratch[FEF_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -197,7 +204,7 @@ namespace {
 constexpr int kPhaseTopN = 3;  // internal: draft rows only, then the baseline's top-n selection
 fef_status run_step(const fef_params* prm, int phase, int n_transfer, const void* h_draft, const void* h_target,
                     const void* W_vocab, int32_t K, int32_t block, uint64_t seed, int32_t* out_tokens,
-                    int32_t* out_accept_len, uint8_t* out_remask);
+                    int32_t* out_accept_len, uint8_t* out_remask, void* workspace, size_t workspace_bytes);
 }  // namespace
 
 fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const void* h_target,
@@ -205,7 +212,46 @@ fef_status fef_verify_step(const fef_params* prm, const void* h_draft, const voi
                            int32_t* out_tokens, int32_t* out_accept_len, uint8_t* out_remask) {
   if (!prm) return fail(FEF_ERR_INVALID_ARG, "params is NULL");
   return run_step(prm, prm->phase, 0, h_draft, h_target, W_vocab, K, block, seed, out_tokens, out_accept_len,
-                  out_remask);
+                  out_remask, prm->workspace, prm->workspace_bytes);
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device, NULL = not asked yet
+
+// Address of this device's copy of `scratch`; resolved once per device with that device current.
+fef_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(FEF_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(FEF_ERR_UNSUPPORTED, "device index %d out of range", dev);
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(FEF_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // concurrent first calls store the same address
+  }
+  *out = ptr;
+  return FEF_OK;
+}
+}  // namespace
+
+fef_status fef_verify_step_static(const fef_params* prm, const void* h_draft, const void* h_target,
+                                  const void* W_vocab, int32_t K, int32_t block, uint64_t seed,
+                                  int32_t* out_tokens, int32_t* out_accept_len, uint8_t* out_remask) {
+  if (!prm) return fail(FEF_ERR_INVALID_ARG, "params is NULL");
+  Layout L;
+  fef_status s = make_layout(prm, K, block, &L);
+  if (s != FEF_OK) return s;
+  if (L.total > (size_t)FEF_STATIC_SCRATCH_BYTES)
+    return fail(FEF_ERR_WORKSPACE, "this call needs %zu bytes of scratch, the built-in buffer has %zu: use fef_verify_step "
+                "with a caller workspace", L.total, (size_t)FEF_STATIC_SCRATCH_BYTES);
+  void* ptr = nullptr;
+  s = static_scratch(&ptr);
+  if (s != FEF_OK) return s;
+  return run_step(prm, prm->phase, 0, h_draft, h_target, W_vocab, K, block, seed, out_tokens, out_accept_len,
+                  out_remask, ptr, (size_t)FEF_STATIC_SCRATCH_BYTES);
 }
 
 fef_status fef_topn_step(const fef_params* prm, const void* h, const void* W_vocab, int32_t K, int32_t block,
@@ -219,13 +265,13 @@ fef_status fef_topn_step(const fef_params* prm, const void* h, const void* W_voc
   fef_params p = *prm;
   p.phase = FEF_PHASE_DRAFT;  // sizes, kernel choice and workspace layout of a call over B*K rows
   return run_step(&p, kPhaseTopN, n_transfer, h, nullptr, W_vocab, K, block, seed, out_tokens, out_committed,
-                  out_remask);
+                  out_remask, p.workspace, p.workspace_bytes);
 }
 
 namespace {
 fef_status run_step(const fef_params* prm, int phase, int n_transfer, const void* h_draft, const void* h_target,
                     const void* W_vocab, int32_t K, int32_t block, uint64_t seed, int32_t* out_tokens,
-                    int32_t* out_accept_len, uint8_t* out_remask) {
+                    int32_t* out_accept_len, uint8_t* out_remask, void* workspace, size_t workspace_bytes) {
   Layout L;
   fef_status s = make_layout(prm, K, block, &L);
   if (s != FEF_OK) return s;
@@ -238,12 +284,12 @@ fef_status run_step(const fef_params* prm, int phase, int n_transfer, const void
     return fail(FEF_ERR_INVALID_ARG, "h_draft, h_target and W_vocab must be 16-byte aligned");
   if (!prm->ev_head_begin != !prm->ev_head_end)
     return fail(FEF_ERR_INVALID_ARG, "ev_head_begin and ev_head_end must be given together");
-  if (!prm->workspace) return fail(FEF_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", L.total);
-  if ((uintptr_t)prm->workspace & 255) return fail(FEF_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-  if (prm->workspace_bytes < L.total)
-    return fail(FEF_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", prm->workspace_bytes, L.total);
+  if (!workspace) return fail(FEF_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", L.total);
+  if ((uintptr_t)workspace & 255) return fail(FEF_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < L.total)
+    return fail(FEF_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
 
-  char* ws = (char*)prm->workspace;
+  char* ws = (char*)workspace;
   hipStream_t stream = (hipStream_t)prm->stream;
 
   fef::HeadArgs h{};
