@@ -60,28 +60,37 @@ def head_bytes(wl, skinny, M):
     return wl.V * wl.d * esz + M * wl.d * esz + M * wl.V * 4 + M * nT * 8
 
 
-def cpu_baseline(wl, W, rounds, seed, budget_s=20.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same rounds."""
+def cpu_baseline(wl, W, rounds, seed, budget_s=14.0, budget_1t_s=8.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same rounds: once with
+    every thread the numerical library uses by default, once pinned to one thread."""
     import numpy as np
-    from threadpoolctl import threadpool_info
+    from threadpoolctl import threadpool_info, threadpool_limits
     from oracle import fef_oracle as O
     from paper_2605_14305_amd import synth
     W64 = synth.to_f64(W)
     nb = min(wl.B, max(1, 16 // wl.K))   # batched workloads: a leading subset of sequences
     h64 = [(synth.to_f64(hd[:nb]), synth.to_f64(ht[:nb])) for hd, ht in rounds]
     O.verify_step(h64[0][0], h64[0][1], W64, wl.K, wl.block, seed, temperature=wl.temperature)  # warm-up
-    n, t0 = 0, time.perf_counter()
-    while True:
-        hd, ht = h64[n % len(h64)]
-        O.verify_step(hd, ht, W64, wl.K, wl.block, seed, step=n, temperature=wl.temperature)
-        n += 1
-        el = time.perf_counter() - t0
-        if el > budget_s or n >= 64:
-            break
+
+    def timed(budget, cap):
+        n, t0 = 0, time.perf_counter()
+        while True:
+            hd, ht = h64[n % len(h64)]
+            O.verify_step(hd, ht, W64, wl.K, wl.block, seed, step=n, temperature=wl.temperature)
+            n += 1
+            el = time.perf_counter() - t0
+            if el > budget or n >= cap:
+                return n, el
+
+    n, el = timed(budget_s, 64)
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    with threadpool_limits(limits=1):
+        n1, el1 = timed(budget_1t_s, 16)
     return {"value": nb * wl.K * n / el, "unit": "positions/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{n} verify steps of workload {wl.name} ({nb} of {wl.B} sequences, {nb * wl.K} positions each), "
-                      f"numpy fp64, {el:.1f} s; host has {len(os.sched_getaffinity(0))} usable cores"}
+                      f"numpy fp64, {el:.1f} s; host has {len(os.sched_getaffinity(0))} usable cores",
+            "one_thread": {"value": nb * wl.K * n1 / el1, "unit": "positions/s", "cores": 1,
+                           "sample": f"{n1} of the same steps with the numerical library pinned to one thread, {el1:.1f} s"}}
 
 
 def acceptance_sweep(args, wl, Wd, dev):
@@ -205,8 +214,13 @@ def main():
     ap.add_argument("--sweep", type=int, default=0, metavar="N",
                     help="instead of the timed step, run the acceptance sweep (rho x tau, N calls each) on the "
                          "workload's shape and print its table as one JSON line")
-    ap.add_argument("--events", choices=["inline", "separate"], default="inline",
-                    help="record the head-kernel events inside the timed steps, or in a second pass")
+    ap.add_argument("--events", choices=["inline", "separate"], default="separate",
+                    help="record the head-kernel events in a second pass over the same steps (default: the timed "
+                         "region then holds no event-carrying dispatch), or inside the timed steps")
+    ap.add_argument("--mfma-leg", default="sweep_b64", metavar="WORKLOAD",
+                    help="batched workload of the second timed leg printed under \"mfma\" when the main workload "
+                         "is llada_b1 (same head shape); `none` skips it")
+    ap.add_argument("--mfma-steps", type=int, default=48, help="timed steps of the second leg")
     ap.add_argument("--event-every", type=int, default=4, metavar="N",
                     help="with inline events, attach them to every N-th timed step (a dispatch with events "
                          "costs about 10 us of queue time, which would otherwise sit in every step)")
@@ -237,6 +251,42 @@ def main():
         return bench_cross_entropy(args, wl, W, Wd, dev)
     if args.sweep:
         return acceptance_sweep(args, wl, Wd, dev)
+    out, rounds = time_verify(args, wl, Wd, dev, args.steps, args.warmup)
+    line = {
+        "metric": "verify-step positions/s at d=4096,V=126464 bf16; % HBM (B=1) / % MFMA (B>=32)",
+        "value": out["positions_per_s"],
+        "unit": "positions/s",
+        "n_gpus": 1, "steps": out["steps"], "warmup": args.warmup,
+        "ms_per_step": out["ms_per_step"],
+        "committed_positions_per_s": out["committed_positions_per_s"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": out["config"],
+        "roofline": out["roofline"],
+    }
+    # The batched half of the metric (rows through the head >> the bf16 ridge of ~312): a second,
+    # shorter timed leg on the acceptance-sweep shape, same head W (same d, V, seed).
+    if args.mfma_leg != "none" and wl.name == "llada_b1" and not (args.split or args.graph):
+        wl2 = synth.WORKLOADS[args.mfma_leg]
+        assert (wl2.d, wl2.V, wl2.dtype) == (wl.d, wl.V, wl.dtype), "the second leg reuses the resident head"
+        out2, _ = time_verify(args, wl2, Wd, dev, args.mfma_steps, max(2, args.warmup // 3))
+        line["mfma"] = {"workload": wl2.name, "steps": out2["steps"], "ms_per_step": out2["ms_per_step"],
+                        "positions_per_s": out2["positions_per_s"],
+                        "committed_positions_per_s": out2["committed_positions_per_s"],
+                        "config": out2["config"], "roofline": out2["roofline"]}
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, W, rounds, args.seed)
+    print(json.dumps(line), flush=True)
+
+
+def time_verify(args, wl, Wd, dev, steps, warmup):
+    """Time `steps` calls of fef_verify_step on workload `wl` (head Wd resident) after `warmup`
+    untimed ones; the head kernel's own duration comes from HIP events the library attaches to
+    that dispatch, by default in a second pass over the same steps so that no event-carrying
+    dispatch sits in the timed region.  Returns (result dict, host copies of the hidden states)."""
+    import torch
+    from paper_2605_14305_amd import binding as fb
+    from paper_2605_14305_amd import synth
     n_rounds = 16   # distinct hidden-state batches, cycled, so only W could ever sit in a cache
     rounds = [synth.make_round(wl, args.seed, block_index=i // 8, step=i) for i in range(n_rounds)]
     rounds_d = [(hd.to(dev), ht.to(dev)) for hd, ht in rounds]
@@ -246,7 +296,7 @@ def main():
     p0.phase = fb.FEF_PHASE_DRAFT if args.split else fb.FEF_PHASE_FUSED
     variant = fb.fef_select_gemm(p0, wl.K)
     ev = HipEvents()
-    pairs = [(ev.create(), ev.create()) for _ in range(max(args.steps, 16))]
+    pairs = [(ev.create(), ev.create()) for _ in range(max(steps, 16))]
 
     def step(i, events=None):
         hd, ht = rounds_d[i % n_rounds]
@@ -257,7 +307,7 @@ def main():
         else:
             vs(hd, ht, Wd, args.seed, step=i, temperature=wl.temperature, head_events=events)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     inline = args.events == "inline" and not args.graph
@@ -271,8 +321,8 @@ def main():
         with torch.cuda.graph(graph):
             for i in range(n_rounds):
                 step(i)
-        replays = max(1, args.steps // n_rounds)
-        args.steps = replays * n_rounds
+        replays = max(1, steps // n_rounds)
+        steps = replays * n_rounds
         graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -282,24 +332,26 @@ def main():
         elapsed = time.perf_counter() - t0
     else:
         t0 = time.perf_counter()
-        for i in range(args.steps):
+        for i in range(steps):
             step(i, pairs[i] if inline and i % args.event_every == 0 else None)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
     if not inline:
-        for i in range(args.steps):
+        for i in range(steps):
             step(i, pairs[i])
         torch.cuda.synchronize()
-    sampled = range(0, args.steps, args.event_every) if inline else range(args.steps)
+    sampled = range(0, steps, args.event_every) if inline else range(steps)
     head_ms = [ev.elapsed_ms(*pairs[i]) for i in sampled]
     head_avg_s = sum(head_ms) / len(head_ms) / 1e3
+    for a, b in pairs:
+        ev.destroy(a); ev.destroy(b)
 
     # Outside the timed region: positions committed by the same steps (the decisions are a function
     # of inputs and seed, so a second pass repeats them), and the rate of a plain read of W.
     committed = 0
     if not args.split:
         counts = []
-        for i in range(args.steps):
+        for i in range(steps):
             hd, ht = rounds_d[i % n_rounds]
             tok, _, _ = vs(hd, ht, Wd, args.seed, step=i, temperature=wl.temperature)
             counts.append((tok >= 0).sum())
@@ -315,7 +367,7 @@ def main():
     torch.cuda.synchronize()
     read_ceiling = Wd.numel() * Wd.element_size() * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
-    ms_per_step = elapsed / args.steps * 1e3
+    ms_per_step = elapsed / steps * 1e3
     positions = wl.B * wl.K
     M = positions if args.split else 2 * positions   # rows through one head launch
     hb = head_bytes(wl, variant == fb.FEF_GEMM_SKINNY, M)
@@ -340,31 +392,27 @@ def main():
                  "plain_read_of_W_GBs": read_ceiling})
     if roof["bound"] == "hbm":
         roof["frac_of_plain_read"] = roof["achieved"] / read_ceiling
+    # HBM-side bytes per launch are profiler counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) of an
+    # earlier run of this same command, stored with the profiles; they are not measured in this run.
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
             t = json.load(f).get(f"{roof['kernel']}:{wl.name}")
         if t:
             roof["traffic"] = t["hbm_bytes_per_launch"]
-
+            roof["traffic_source"] = "profiles/traffic.json (stored rocprofv3 counter run of this kernel and workload)"
     out = {
-        "metric": "verify-step positions/s at d=4096,V=126464 bf16; % HBM (B=1) / % MFMA (B>=32)",
-        "value": positions / (elapsed / args.steps),
-        "unit": "positions/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "steps": steps, "ms_per_step": ms_per_step, "positions_per_s": positions / (elapsed / steps),
         "committed_positions_per_s": committed / elapsed if committed else None,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "K": wl.K, "block": wl.block, "d": wl.d, "V": wl.V,
                    "rho": wl.rho, "logit_std": wl.logit_std, "temperature": wl.temperature,
                    "rows_through_head": M, "call_order": "draft+target" if args.split else "fused",
                    "launch": "hip graph replay" if args.graph else "stream"},
         "roofline": roof,
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, W, rounds, args.seed)
-    print(json.dumps(out), flush=True)
+    del vs
+    torch.cuda.empty_cache()
+    return out, rounds
 
 
 if __name__ == "__main__":

@@ -29,12 +29,26 @@ def _case(R, d, V, dtype="bf16", variant=fb.FEF_GEMM_AUTO, seed=0, temperature=1
     return out.cpu().numpy().astype(np.float64), float(loss.cpu()[0]), h, W, labels
 
 
+def ce_tolerance(d, temperature=1.0, logit_std=3.0):
+    """Bound on |CE_gpu - CE_oracle| from the arithmetic: CE = lse - L[label].
+    A logit is a sum of d products that are exact in fp32 (bf16 x bf16), accumulated in fp32: d
+    roundings of at most 2^-24 |partial sum| each, independent and zero-mean, partial sums below
+    5 standard deviations of the scaled logit: E_L = 6 sqrt(d/3) 2^-24 (5 logit_std / tau) (six
+    sigma of the accumulated rounding).  lse is 1-Lipschitz in the maximum norm, so the logit errors
+    move it by at most E_L; evaluating it in fp32 (exp to 2 ulp, tree sums over V terms, log, one
+    addition at |lse| < 32) and the final subtraction add less than 5e-6."""
+    e_l = 6.0 * np.sqrt(d / 3.0) * 2.0 ** -24 * (5.0 * logit_std / temperature)
+    return 2.0 * e_l + 5e-6
+
+
 def _check(got, loss, h, W, labels, temperature=1.0, rows=None):
     rows = np.arange(len(labels)) if rows is None else rows
     want, _ = C.cross_entropy(synth.to_f64(h[rows]), synth.to_f64(W), labels[rows], temperature)
     err = np.abs(got[rows] - want)
-    assert np.all(err <= 2e-2 * np.abs(want) + 5e-4)        # the tolerance of logits and log-sum-exp
-    assert err.max() <= 5e-4, err.max()                       # what the fp32 path actually delivers
+    tol = ce_tolerance(h.shape[1], temperature)               # 4.0e-4 at d = 4096, tau = 1
+    assert tol <= 5e-4 / min(1.0, temperature)
+    assert np.all(err <= 2e-2 * np.abs(want) + 1e-6)          # the stated ceiling for logits and probabilities
+    assert err.max() <= tol, (err.max(), tol)
     assert np.all(got[labels < 0] == 0.0)
     return want
 

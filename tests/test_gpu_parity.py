@@ -158,12 +158,16 @@ def test_llada_shape_through_the_streaming_kernel(llada_head, B):
     hd, ht = synth.make_hidden(B, K, wl.d, 9, wl.rho, wl.sigma_h, "bf16", 0, 2)
     tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 9, step=2)
     torch.cuda.synchronize()
+    equal = near = 0
     for b in [0, 3, B - 1]:
         r = O.verify_step(synth.to_f64(hd[b:b + 1]), synth.to_f64(ht[b:b + 1]), W64, K, block, 9, step=2,
                           seq_base=b)
         diag = {k: _np(v)[b:b + 1] if k != "lse" else _np(v)[:, b:b + 1] for k, v in vs.diag.items()}
         st = parity.compare(r, _np(tok)[b:b + 1], _np(acc)[b:b + 1], _np(rem)[b:b + 1], diag)
+        equal += st["equal"]; near += st["near_margin"]
         print(f"seq {b}: {st}", flush=True)
+    print(f"B={B}: {equal} of 3 sampled sequences identical, {near} near-margin", flush=True)
+    assert equal >= 2
 
 
 def test_maximum_window_and_block():
@@ -445,12 +449,16 @@ def test_llada_shape_batched_subset(llada_head):
     tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 3, step=5)
     torch.cuda.synchronize()
     # sequence ids differ per picked row, so the oracle runs them one at a time with seq_base
+    equal = near = 0
     for b in [0, 7, 15]:
         r = O.verify_step(synth.to_f64(hd[b:b + 1]), synth.to_f64(ht[b:b + 1]), W64, K, block, 3, step=5,
                           seq_base=b)
         diag = {k: _np(v)[b:b + 1] if k != "lse" else _np(v)[:, b:b + 1] for k, v in vs.diag.items()}
         st = parity.compare(r, _np(tok)[b:b + 1], _np(acc)[b:b + 1], _np(rem)[b:b + 1], diag)
+        equal += st["equal"]; near += st["near_margin"]
         print(f"seq {b}: {st}", flush=True)
+    print(f"{equal} of 3 sampled sequences identical, {near} near-margin", flush=True)
+    assert equal >= 2
 
 
 def test_dream_shape_subset():
@@ -474,6 +482,32 @@ def test_dream_shape_subset():
     torch.cuda.synchronize()
     ref1 = O.verify_step(synth.to_f64(hd1), synth.to_f64(ht1), W64, 8, wl.block, 1, step=2)
     parity.compare(ref1, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs1.diag.items()})
+
+
+def test_dream_shape_window_16_batch1_full_size():
+    """Dream-7B-shaped single sequence with the paper's largest window (B=1, K=16, d=3584,
+    V=151936: 32 rows through the head).  AUTO gives it the 32-row streaming kernel at d=3584,
+    whose per-workgroup token runs exceed 512 tokens at this V, so the draft draw inside a tile
+    takes the memory-resident path.  Every output element against the oracle."""
+    wl = synth.WORKLOADS["dream_b32"]
+    W = synth.make_head(wl.V, wl.d, 3, "bf16")
+    Wd, W64 = W.to(DEV), synth.to_f64(W)
+    vs = fb.VerifyStep(1, wl.K, wl.block, wl.d, wl.V, device=DEV, diag=True, diag_logits=True)
+    assert fb.fef_select_gemm(vs._params(), wl.K) == fb.FEF_GEMM_SKINNY
+    equal = flipped = 0
+    acc_lens = []
+    for step in range(3):
+        hd, ht = synth.make_round(wl, 3, block_index=step % 2, step=step, B=1)
+        tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 3, step=step, pos_base=64 * (step % 2))
+        torch.cuda.synchronize()
+        ref = O.verify_step(synth.to_f64(hd), synth.to_f64(ht), W64, wl.K, wl.block, 3, step=step,
+                            pos_base=64 * (step % 2), return_logits=True)
+        st = parity.compare(ref, _np(tok), _np(acc), _np(rem), {k: _np(v) for k, v in vs.diag.items()})
+        equal += st["equal"]; flipped += st["near_flipped"]
+        acc_lens.append(int(ref.accept_len[0]))
+        print(f"step {step}: accept_len {ref.accept_len[0]} alpha {ref.alpha[0].round(3)} {st}", flush=True)
+    assert equal >= 2 and flipped <= 1
+    assert st["draft_slots"] == wl.K and st["draft_near"] <= 2      # the draft draws were compared slot by slot
 
 
 def test_dream_shape_full_batch_sampled():
