@@ -94,8 +94,8 @@ def cpu_baseline(wl, W, rounds, seed, budget_s=14.0, budget_1t_s=8.0):
 
 
 def acceptance_sweep(args, wl, Wd, dev):
-    """The acceptance-rate sweep of the batched configuration: for draft/target correlations rho and
-    temperatures tau, `--sweep N` calls each; reports the mean overlap alpha = sum min(p, q) the calls
+    """The acceptance-rate sweep of the batched configuration: for draft/target correlations rho (0.999
+    added to the stated three so that the mean overlap reaches ~0.95) and temperatures tau, `--sweep N` calls each; reports the mean overlap alpha = sum min(p, q) the calls
     return, the mean committed length they produce, the closed form (1 - alpha^K) / (1 - alpha) of
     Theorem 2 at that mean alpha, and the idealised acceleration S = E[C] / 2 (Corollary 2)."""
     import torch
@@ -103,7 +103,7 @@ def acceptance_sweep(args, wl, Wd, dev):
     from paper_2605_14305_amd import synth
     vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, dtype=wl.dtype, device=dev, diag=True)
     rows = []
-    for rho in (0.5, 0.9, 0.99):
+    for rho in (0.5, 0.9, 0.99, 0.999):
         batches = [tuple(t.to(dev) for t in synth.make_hidden(wl.B, wl.K, wl.d, args.seed, rho, wl.sigma_h, wl.dtype, 0, r))
                    for r in range(8)]
         for tau in (0.5, 1.0):

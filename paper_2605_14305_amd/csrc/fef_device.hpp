@@ -85,6 +85,8 @@ constexpr int kResidChunk = 256;  // vocabulary entries per residual-mass chunk
 
 struct SeqState {
   int window, acc_len;
+  float rej_lse_q, rej_lse_p;  // log-sum-exps of the rejected slot's draft / target row (if acc_len < window)
+  int rej_pos, rej_xtarget;    // its block offset; greedy variant: the arg max of its target row
   int x[kMaxK];       // draft tokens of the window
   float ptok[kMaxK];  // pi(x~)
 };

@@ -28,6 +28,21 @@ namespace {
 //   B (32 x 16): lane holds B[8g .. 8g+7][i]        -> H row i, the same k range
 //   D (16 x 16): lane holds D[4g + r][i], r = 0..3  -> logits of 4 consecutive tokens, row i
 // ---------------------------------------------------------------------------------------------
+#ifndef FEF_NT_LOGITS
+#define FEF_NT_LOGITS 1
+#endif
+// The logits of a workgroup leave in one burst at its end, i.e. all 8 to 16 MB of them in the last
+// microseconds of the kernel.  Written as ordinary stores they would sit dirty in L2 until the
+// write-back that closes the kernel, which the next kernel has to wait for; non-temporal stores
+// go through to memory at once.
+__device__ inline void store_logit(float* p, float v) {
+#if FEF_NT_LOGITS
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
+#endif
+}
+
 constexpr int kSkinnyWaves = 8;
 constexpr int kSkinnyOutTiles = 40;  // tiles of logits staged in LDS before a flush
 constexpr int kSkinnyThreads = kSkinnyWaves * kWave;
@@ -138,7 +153,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
       const int v0 = tflush * 16, nv = min(tend * 16, a.V) - v0;
       __syncthreads();
       for (int r = wave; r < M; r += kSkinnyWaves)
-        for (int i = lane; i < nv; i += kWave) a.logits[(size_t)r * a.ldl + v0 + i] = out[r][i];
+        for (int i = lane; i < nv; i += kWave) store_logit(&a.logits[(size_t)r * a.ldl + v0 + i], out[r][i]);
       __syncthreads();
       tflush = tend;
     }
@@ -268,7 +283,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny32_kernel(HeadArgs 
       const int v0 = tflush * 16, nv = min(tend * 16, a.V) - v0;
       __syncthreads();
       for (int r = wave; r < M; r += kSkinnyWaves)
-        for (int i = lane; i < nv; i += kWave) a.logits[(size_t)r * a.ldl + v0 + i] = out[r][i];
+        for (int i = lane; i < nv; i += kWave) store_logit(&a.logits[(size_t)r * a.ldl + v0 + i], out[r][i]);
       __syncthreads();
       tflush = tend;
     }

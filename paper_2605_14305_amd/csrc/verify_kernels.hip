@@ -389,8 +389,11 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
 // Final phase for one sequence (one workgroup): residual sample, commit, mask update, LowConf.
 // ---------------------------------------------------------------------------------------------
 
+// rm_pre: (wavefront 0 only) the residual chunk masses of this sequence, 16 per lane, loaded by the
+// caller before the accept-phase results were known; valid if have_pre.
 __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st, BlockTmp& tmp,
-                                  float* s_conf, uint8_t* s_mask, uint8_t* s_cand) {
+                                  float* s_conf, uint8_t* s_mask, uint8_t* s_cand, const float (&rm_pre)[16],
+                                  bool have_pre) {
   const int tid = threadIdx.x;
   const int BK = a.B * a.K;
   const int window = st.window, acc_len = st.acc_len;
@@ -422,12 +425,15 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
     const int s = b * a.K + acc_len;
     const float* Lq = a.logits + (size_t)s * a.ldl;
     const float* Lp = a.logits + (size_t)(BK + s) * a.ldl;
-    const float lse_q = a.lse[s], lse_p = a.lse[BK + s];
+    // log-sum-exps, position and target arg max of the rejected slot travel with the accept-phase
+    // results, so nothing here waits for a load whose address depends on acc_len except the logits
+    const float lse_q = st.rej_lse_q, lse_p = st.rej_lse_p;
     const float* rm = a.rmass + (size_t)(a.all_slots ? s : b) * a.nRC;
-    const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
+    const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)st.rej_pos, a.step,
                                    a.seq_base + (uint32_t)b, kStreamResidual);
     if (a.greedy) {
-      z = a.xtarget[s];  // residual of two point masses: the target's
+      z = st.rej_xtarget;  // residual of two point masses: the target's
+      z_conf = expf(Lp[z] - lse_p);
     } else if (a.nRC <= kWave * kChunkPer) {
       // one wavefront, everything in registers
       if (tid < kWave) {
@@ -435,10 +441,11 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
 #pragma unroll
         for (int j = 0; j < kChunkPer; ++j) {
           const int c = tid * kChunkPer + j;
-          rmv[j] = c < a.nRC ? rm[c] : 0.f;
+          rmv[j] = have_pre ? rm_pre[j] : (c < a.nRC ? rm[c] : 0.f);
         }
         const Found chunk = wave_find_first_reg<kChunkPer, true>(rmv, u);
         int zz;
+        float zc;
         if (chunk.total > 0.f) {
           const int v0 = chunk.idx * kResidChunk + tid * 4;
           float qv[4] = {0.f, 0.f, 0.f, 0.f}, pv[4] = {0.f, 0.f, 0.f, 0.f};
@@ -451,12 +458,18 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
             for (int j = 0; j < 4; ++j)
               if (v0 + j < a.V) { qv[j] = Lq[v0 + j]; pv[j] = Lp[v0 + j]; }
           }
-          float rv[4];
+          float rv[4], pe[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            rv[j] = v0 + j < a.V ? fmaxf(expf(pv[j] - lse_p) - expf(qv[j] - lse_q), 0.f) : 0.f;
+          for (int j = 0; j < 4; ++j) {
+            pe[j] = expf(pv[j] - lse_p);
+            rv[j] = v0 + j < a.V ? fmaxf(pe[j] - expf(qv[j] - lse_q), 0.f) : 0.f;
+          }
           const Found in = wave_find_first_reg<4>(rv, u * chunk.total - chunk.before);
           zz = chunk.idx * kResidChunk + in.idx;
+          // pi(z) from the lane that holds token z: no second trip to memory
+          const int j = in.idx & 3;
+          const float mine = j == 0 ? pe[0] : j == 1 ? pe[1] : j == 2 ? pe[2] : pe[3];
+          zc = __shfl(mine, in.idx >> 2, 64);
         } else {
           // residual mass vanished in rounding although a rejection occurred: commit argmax pi
           float best = -INFINITY;
@@ -467,11 +480,13 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
           }
           const float gbest = wave_max(best);
           zz = wave_min_int(best == gbest ? bi : INT_MAX);
+          zc = expf(Lp[zz] - lse_p);
         }
-        if (tid == 0) tmp.bcast_i = zz;
+        if (tid == 0) { tmp.bcast_i = zz; tmp.bcast_f = zc; }
       }
       __syncthreads();
       z = tmp.bcast_i;
+      z_conf = tmp.bcast_f;
     } else {
     float Z = 0.f;
     {
@@ -504,8 +519,8 @@ __device__ void finalize_sequence(const VerifyArgs& a, int b, const SeqState& st
       const float gbest = block_max(best, tmp);
       z = block_min_int(best == gbest ? bi : INT_MAX, tmp);
     }
-    }
     z_conf = expf(Lp[z] - lse_p);
+    }
   }
 
   // commit tokens and confidences
@@ -602,24 +617,35 @@ __global__ __launch_bounds__(NT) void accept_resid_kernel(VerifyArgs a) {
   const int window = a.window[b];
 
   if (wave == 0) {
+    // everything whose address is known up front is requested together (slots beyond the window
+    // hold x = -1 and are not used); only the two gathers at x~ wait for a previous load
+    const int sl = b * a.K + min(lane, a.K - 1);
+    const int x = a.xdraft[sl], pos = a.slot_pos[sl];
+    const float lse_q = a.lse[sl], lse_p = a.lse[BK + sl];
+    const int xt = a.greedy ? a.xtarget[sl] : -1;
     bool rejected = false;
     if (lane < window) {
-      const int s = b * a.K + lane;
-      const int x = a.xdraft[s];
-      const float lq = a.logits[(size_t)s * a.ldl + x] - a.lse[s];
-      const float lp = a.logits[(size_t)(BK + s) * a.ldl + x] - a.lse[BK + s];
+      const float lq = a.logits[(size_t)sl * a.ldl + x] - lse_q;
+      const float lp = a.logits[(size_t)(BK + sl) * a.ldl + x] - lse_p;
       const float ratio = fminf(1.f, expf(lp - lq));
-      const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)a.slot_pos[s], a.step,
+      const float u = philox_uniform(a.seed, a.pos_base + (uint32_t)pos, a.step,
                                      a.seq_base + (uint32_t)b, kStreamAccept);
       // greedy: the ratio of the two point masses is 1 if the arg maxes agree, else 0
-      rejected = a.greedy ? x != a.xtarget[s] : !(u <= ratio);
+      rejected = a.greedy ? x != xt : !(u <= ratio);
       st.x[lane] = x;
       st.ptok[lane] = expf(lp);
     }
     const unsigned long long rej = __ballot(rejected);
+    const int acc = rej ? __ffsll((long long)rej) - 1 : window;
     if (lane == 0) {
       st.window = window;
-      st.acc_len = rej ? __ffsll((long long)rej) - 1 : window;
+      st.acc_len = acc;
+    }
+    if (lane == acc && acc < window) {  // the rejected slot's own values, for the final phase
+      st.rej_lse_q = lse_q;
+      st.rej_lse_p = lse_p;
+      st.rej_pos = pos;
+      st.rej_xtarget = xt;
     }
   }
   __syncthreads();
@@ -673,11 +699,22 @@ __global__ __launch_bounds__(NT) void finalize_kernel(VerifyArgs a) {
   __shared__ SeqState st;
   __shared__ float s_conf[kMaxBlock];
   __shared__ uint8_t s_mask[kMaxBlock], s_cand[kMaxBlock];
-  const int b = blockIdx.x;
-  if (threadIdx.x < (int)(sizeof(SeqState) / 4))
-    reinterpret_cast<int*>(&st)[threadIdx.x] = reinterpret_cast<const int*>(a.seqstate + b)[threadIdx.x];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  int word = 0;
+  if (tid < (int)(sizeof(SeqState) / 4)) word = reinterpret_cast<const int*>(a.seqstate + b)[tid];
+  // Without the diagnostics the chunk masses of a sequence sit at an address that does not depend
+  // on which slot was rejected: wavefront 0 asks for them in the same breath as the accept-phase
+  // results (when nothing was rejected they are stale and unused).
+  float rm_pre[kChunkPer];
+  const bool have_pre = !a.all_slots && !a.greedy && a.nRC <= kWave * kChunkPer;
+#pragma unroll
+  for (int j = 0; j < kChunkPer; ++j) {
+    const int c = tid * kChunkPer + j;
+    rm_pre[j] = (have_pre && tid < kWave && c < a.nRC) ? a.rmass[(size_t)b * a.nRC + c] : 0.f;
+  }
+  if (tid < (int)(sizeof(SeqState) / 4)) reinterpret_cast<int*>(&st)[tid] = word;
   __syncthreads();
-  finalize_sequence(a, b, st, tmp, s_conf, s_mask, s_cand);
+  finalize_sequence(a, b, st, tmp, s_conf, s_mask, s_cand, rm_pre, have_pre);
 }
 
 // ---------------------------------------------------------------------------------------------

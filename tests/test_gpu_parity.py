@@ -540,7 +540,8 @@ def test_dream_shape_full_batch_sampled():
 
 
 def test_acceptance_sweep_matches_theorem_2(llada_head):
-    """Acceptance-rate sweep at scale (B=64, K=16, d=4096, V=126464): for each (rho, tau) the mean
+    """Acceptance-rate sweep at scale (B=64, K=16, d=4096, V=126464; rho = 0.999 added to the stated
+    three so that the mean overlap reaches ~0.95, where Theorem 2's E[C_16] ~ 11): for each (rho, tau) the mean
     committed length of the HIP path matches Theorem 2 evaluated on the per-slot acceptance
     probabilities alpha = sum min(p, q) that the same call reports, and sampled sequences match the
     oracle.  Prints mean alpha, mean C, E[C_k] and the idealised acceleration E[C_k]/2."""
@@ -548,7 +549,7 @@ def test_acceptance_sweep_matches_theorem_2(llada_head):
     B, K, block = 64, 16, 32
     vs = fb.VerifyStep(B, K, block, wl.d, wl.V, device=DEV, diag=True)
     alphas_seen = []
-    for rho in (0.5, 0.9, 0.99):
+    for rho in (0.5, 0.9, 0.99, 0.999):
         for tau in (0.5, 1.0):
             C, EC, al = [], [], []
             for step in range(3):
@@ -571,7 +572,7 @@ def test_acceptance_sweep_matches_theorem_2(llada_head):
                   f"Theorem-2 E[C] {EC.mean():.3f}  S=E[C]/2 {EC.mean() / 2:.3f}  (n={C.size})", flush=True)
             assert abs(C.mean() - EC.mean()) < 4 * se + 0.02
             alphas_seen.append(np.mean(al))
-    assert min(alphas_seen) < 0.35 and max(alphas_seen) > 0.8     # the sweep spans low and high acceptance
+    assert min(alphas_seen) < 0.2 and max(alphas_seen) > 0.93     # the sweep spans the stated range of overlaps, ~0.2 to ~0.95
 
 
 @pytest.mark.parametrize("B,K,d,V", [(1, 8, 512, 3000), (6, 8, 256, 2050), (40, 4, 128, 700)])
