@@ -74,7 +74,8 @@ typedef enum {
  * in this call: 2*B*K fused, B*K in a DRAFT or TARGET call. */
 typedef enum {
   FEF_GEMM_AUTO = 0,
-  FEF_GEMM_SKINNY = 1, /* bf16, M <= 32, d in {512, 3584, 4096}: W streamed once, split-k  */
+  FEF_GEMM_SKINNY = 1, /* bf16, M <= 32, d in {512, 1024, 2048, 2560, 3072, 3584, 4096}: W streamed
+                          once, split-k; other d at M <= 32 go to STREAM (fef_select_gemm tells) */
   FEF_GEMM_TILED = 2,  /* bf16, any M: plain 128x128 LDS-tiled MFMA GEMM (never picked by AUTO) */
   FEF_GEMM_F32 = 3,    /* f32, any shape: reference-grade FMA kernel                       */
   FEF_GEMM_TILED256 = 4, /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)       */

@@ -79,7 +79,7 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
   switch (v) {
     case FEF_GEMM_SKINNY:
       if (p->dtype != FEF_BF16 || !fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d))
-        return fail(FEF_ERR_UNSUPPORTED, "skinny head kernel needs bf16, at most 32 rows through the head and d in {512, 3584, 4096}");
+        return fail(FEF_ERR_UNSUPPORTED, "skinny head kernel needs bf16, at most 32 rows through the head and d in {512, 1024, 2048, 2560, 3072, 3584, 4096}");
       break;
     case FEF_GEMM_TILED:
     case FEF_GEMM_TILED256:

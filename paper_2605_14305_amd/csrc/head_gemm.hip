@@ -443,38 +443,32 @@ __global__ __launch_bounds__(kWave) void head_f32_kernel(HeadArgs a) {
 
 }  // namespace
 
-bool skinny_supports(int M, int d) { return M <= 32 && (d == 512 || d == 3584 || d == 4096); }
+// The eight wavefronts split k into slices of 32 KS columns held in registers: d = 256 KS with KS
+// fixed at compile time; instantiated for the hidden sizes below.
+#define FEF_SKINNY_SIZES(X) X(512, 2) X(1024, 4) X(2048, 8) X(2560, 10) X(3072, 12) X(3584, 14) X(4096, 16)
+
+bool skinny_supports(int M, int d) {
+  if (M > 32) return false;
+#define FEF_X(D, KS) if (d == D) return true;
+  FEF_SKINNY_SIZES(FEF_X)
+#undef FEF_X
+  return false;
+}
 
 template <int NB>
 hipError_t launch_head_skinny_nb(const HeadArgs& a) {
   const int tiles = (a.V + kSkinnyUnit - 1) / kSkinnyUnit;
   const int grid = a.nT;  // = min(tiles, kSkinnyMaxGrid): one partial per (row, workgroup)
-  if (a.nrows > 16) {
-    switch (a.d) {
-      case 512:
-        FEF_LAUNCH_HEAD((head_skinny32_kernel<2, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
-        break;
-      case 3584:
-        FEF_LAUNCH_HEAD((head_skinny32_kernel<14, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
-        break;
-      case 4096:
-        FEF_LAUNCH_HEAD((head_skinny32_kernel<16, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
-        break;
-      default:
-        return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-  }
   switch (a.d) {
-    case 512:
-      FEF_LAUNCH_HEAD((head_skinny_kernel<2, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
-      break;
-    case 3584:
-      FEF_LAUNCH_HEAD((head_skinny_kernel<14, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
-      break;
-    case 4096:
-      FEF_LAUNCH_HEAD((head_skinny_kernel<16, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);
-      break;
+#define FEF_X(D, KS)                                                                                         \
+  case D:                                                                                                    \
+    if (a.nrows > 16)                                                                                        \
+      FEF_LAUNCH_HEAD((head_skinny32_kernel<KS, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);        \
+    else                                                                                                     \
+      FEF_LAUNCH_HEAD((head_skinny_kernel<KS, NB>), dim3(grid), dim3(kSkinnyThreads), a, a, tiles);          \
+    break;
+    FEF_SKINNY_SIZES(FEF_X)
+#undef FEF_X
     default:
       return hipErrorInvalidValue;
   }

@@ -1,45 +1,53 @@
-// Vocabulary-head kernel for large M = 2*B*K (the batched, MFMA-bound configurations).
+// Vocabulary-head kernel for large M = 2*B*K (the batched configurations).
 //
-// Workgroup tile 256 (rows of H) x 256 (tokens), k-steps of 32; eight wavefronts in a 2 x 4 grid,
-// each 128 x 64 as 4 x 2 v_mfma_f32_32x32x16_bf16 tiles (128 accumulator registers).
+// Workgroup tile 256 (rows of H) x 256 (tokens), eight wavefronts in a 2 x 4 grid, each 128 x 64 as
+// 4 x 2 v_mfma_f32_32x32x16_bf16 tiles (128 accumulator registers), k-steps of 64.
 //
-// Operand slabs go HBM/L2 -> LDS directly (global_load_lds_dwordx4: lane l of a wavefront
-// deposits its 16 bytes at LDS base + 16 l, so one instruction fills 1 KB = 16 rows x 64 B) into
-// a ring of four 32 KB stages, issued three k-steps ahead of their use; no register staging and
-// no ds_write in the main loop.  A stage is [256 rows][4 chunks of 16 B] for A and for B.  The
-// LDS has 64 four-byte banks, i.e. four 64-byte rows per sweep, so chunk c of row r is kept at
-// position c ^ ((r >> 2) & 3): the 16-byte fragment reads of 16 consecutive rows then touch
-// every bank once.  The permutation is applied on the global side (each lane fetches the chunk
-// that belongs in its LDS slot).
+// Operand slabs go HBM/L2 -> LDS directly (global_load_lds_dwordx4: lane l of a wavefront deposits
+// its 16 bytes at LDS base + 16 l): no register staging and no ds_write in the main loop.  A row
+// of a stage is 128 bytes, so one load instruction fetches eight rows of 128 contiguous bytes
+// (whole L2 lines; 64-byte segments move at about 60 % of that rate out of L2), and there is one
+// workgroup barrier per 64 columns of k.  The loads are inline assembly with hand-counted vmcnt
+// before each barrier: with the builtin, the compiler's wait-count pass ties the fragment reads of
+// one stage to the loads in flight for the others.
+//
+// LDS (all 160 KB of the CU): H ring of two 32 KB stages, W ring of three.  H comes from L2 / the
+// Infinity Cache and is requested one k-step ahead; W comes from HBM and is requested two ahead.
+// A stage is [256 rows][8 chunks of 16 B]; the LDS has 64 four-byte banks, i.e. two such rows per
+// sweep, so chunk c of row r is kept at position c ^ ((r >> 1) & 7) and the 16-byte fragment
+// reads of 16 consecutive rows touch every bank once.  The permutation is applied on the global
+// side of the load (lane l lands at LDS base + 16 l and fetches the chunk that belongs there).
+//
+// One k-step is four 16-wide slices.  The fragments of a slice are read while the multiplies of
+// the slice before it run; the last slice of a step is multiplied after the next step's barrier,
+// under the first fragment reads of the new stage, so the barrier does not idle the matrix unit
+// for the latency of those reads.
 //
 // The epilogue works straight from the accumulator registers: for a fixed accumulator index the 32
 // lanes of a half-wavefront hold 32 consecutive tokens of one row, so dword stores write whole
 // 128-byte lines, and the per-row (max, sum exp) over the wavefront's 64 tokens is reduced by DPP.
 //
-// Tile order: workgroup ids go round-robin over the 8 XCDs; within an XCD consecutive
-// workgroups take the row tiles of one token tile, so a W tile comes from HBM once and is
-// shared through that XCD's L2.
+// Tile order: workgroup ids go round-robin over the 8 XCDs; within an XCD consecutive workgroups
+// take the row tiles of one token tile, so a W tile comes from HBM once and is shared through
+// that XCD's L2.
+#include <type_traits>
+
 #include "head_common.hpp"
 
 namespace fef {
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 32;
-constexpr int kStageChunks = (BM + BN) * 4;  // 16-byte chunks per stage: A rows then B rows
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kStage = BM * 8;   // 16-byte chunks per operand stage (BM == BN)
+constexpr int kRingH = 2, kRingW = 3;
 
-// TJ = 32-token tiles per wavefront: 2 -> eight wavefronts of 128 x 64.  (4 -> four wavefronts of
-// 128 x 128, one per SIMD, was measured slower and is not instantiated.)
-template <int TJ, bool CE>
-__global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_kernel(HeadArgs a, int m_tiles, int n_tiles) {
-  constexpr int WN = BN / (32 * TJ);      // wavefronts along the token dimension
-  constexpr int NWAVES = 2 * WN;
-  constexpr int QI = BM / (16 * NWAVES);  // load instructions per operand per wavefront per stage
-  // one array per stage, so the compiler can tell the in-flight LDS writes of the other stages
-  // from the fragment reads of the current one
-  __shared__ bf16x8 st0[kStageChunks], st1[kStageChunks], st2[kStageChunks], st3[kStageChunks];
+template <bool CE>
+__global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_tiles, int n_tiles) {
+  __shared__ bf16x8 ringH[kRingH * kStage];  // 64 KB
+  __shared__ bf16x8 ringW[kRingW * kStage];  // 96 KB
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: LDS offsets of the loads need no lane readback
-  const int wm = wave / WN, wn = wave % WN;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
   const int j32 = lane & 31, h = lane >> 5;
   const int M = a.nrows;
 
@@ -48,174 +56,135 @@ __global__ __launch_bounds__(2 * (BN / (32 * TJ)) * kWave) void head_tiled256_ke
   if (nt >= n_tiles) return;
   const int m0 = mt * BM, n0 = nt * BN;
 
-  // Direct-to-LDS loads: wavefront w fills rows [32 w, 32 w + 32) of A and of B, 16 rows per
-  // instruction; lane l owns LDS slot (row 16 q + l/4, position l%4) and fetches the chunk that
-  // the swizzle assigns to that slot.
-  const __bf16* gp[2 * QI];
+  // Direct-to-LDS loads: wavefront w fills rows [32 w, 32 w + 32) of an H stage and of a W stage,
+  // 8 rows per instruction; lane l owns LDS slot (row 8 q + l / 8, position l % 8).
+  const __bf16* gh[4];
+  const __bf16* gw[4];
 #pragma unroll
-  for (int q = 0; q < QI; ++q) {
-    const int rl = wave * (16 * QI) + q * 16 + (lane >> 2);  // row inside the tile
-    const int c = (lane & 3) ^ ((rl >> 2) & 3);            // logical 16-byte chunk of that row
-    const int r = min(m0 + rl, M - 1);                     // rows past M / V re-read the last
-    const int v = min(n0 + rl, a.V - 1);                   // row; masked in the epilogue
-    gp[q] = h_row(a, r) + c * 8;
-    gp[QI + q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
+  for (int q = 0; q < 4; ++q) {
+    const int rl = wave * 32 + q * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((rl >> 1) & 7);
+    const int r = min(m0 + rl, M - 1);      // rows past M / V re-read the last row; masked in the epilogue
+    const int v = min(n0 + rl, a.V - 1);
+    gh[q] = h_row(a, r) + c * 8;
+    gw[q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
   }
-  // gp[] point at k-step `kbase`; the steady-state loop advances them by one k-step per step
-  // (one 64-bit add per load) instead of forming base + offset each time.
-  int kbase = 0;
-  auto stage_slot = [&](bf16x8* stage, int n) {
-    return lds_offset(stage + (n < QI ? 0 : BM * 4) + (wave * (16 * QI) + (n % QI) * 16) * 4);
+  const uint32_t slotH = lds_offset(ringH + wave * 32 * 8), slotW = lds_offset(ringW + wave * 32 * 8);
+  constexpr uint32_t kStageBytes = kStage * 16;
+  // loads of this wavefront for the k-step the pointers stand at, which then move on by one step
+  auto issue_h = [&](int stage, int q) {
+    load_to_lds_16(gh[q], slotH + stage * kStageBytes + q * 1024);
+    gh[q] += BK;
   };
-  // load n (0 .. 2 QI - 1) of this wavefront for k-step kt: A rows first, then B rows
-  auto issue_one = [&](bf16x8* stage, int kt, int n) {
-    load_to_lds_16(gp[n] + (kt - kbase) * BK, stage_slot(stage, n));
-  };
-  // the same for the k-step gp[n] points at, which then moves on by one
-  auto issue_next = [&](bf16x8* stage, int n) {
-    load_to_lds_16(gp[n], stage_slot(stage, n));
-    gp[n] += BK;
-  };
-  auto issue = [&](bf16x8* stage, int kt) {
-#pragma unroll
-    for (int n = 0; n < 2 * QI; ++n) issue_one(stage, kt, n);
+  auto issue_w = [&](int stage, int q) {
+    load_to_lds_16(gw[q], slotW + stage * kStageBytes + q * 1024);
+    gw[q] += BK;
   };
 
-  floatx16 acc[4][TJ];
+  floatx16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < TJ; ++j) acc[i][j] = floatx16{};
+    for (int j = 0; j < 2; ++j) acc[i][j] = floatx16{};
 
-  // Fragments of one 16-wide k-slice: 4 row tiles of A, 2 token tiles of B.
-  struct Frag { bf16x8 a[4], b[TJ]; };
-  auto read_frag = [&](const bf16x8* stage, int ks, Frag& f) {
-    const bf16x8* As = stage;
-    const bf16x8* Bs = stage + BM * 4;
+  struct Frag { bf16x8 a[4], b[2]; };
+  auto read_frag = [&](const bf16x8* Hs, const bf16x8* Ws, int ks, Frag& f) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) f.a[i] = As[swz4(wm * 128 + i * 32 + j32, ks * 2 + h)];
+    for (int i = 0; i < 4; ++i) f.a[i] = Hs[swz(wm * 128 + i * 32 + j32, ks * 2 + h)];
 #pragma unroll
-    for (int j = 0; j < TJ; ++j) f.b[j] = Bs[swz4(wn * (32 * TJ) + j * 32 + j32, ks * 2 + h)];
+    for (int j = 0; j < 2; ++j) f.b[j] = Ws[swz(wn * 64 + j * 32 + j32, ks * 2 + h)];
   };
-  auto mfma_frag = [&](const Frag& f) {
+  auto mfma_rows = [&](const Frag& f, int i0, int i1) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = i0; i < i1; ++i)
 #pragma unroll
-      for (int j = 0; j < TJ; ++j)
+      for (int j = 0; j < 2; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
   };
 
   const int nk = a.d / BK;
+  const bool idle = m0 + wm * 128 >= M;  // none of this wavefront's rows exists: loads and barriers only
+
+  // prologue: H(0), W(0), W(1)
+#pragma unroll
+  for (int q = 0; q < 4; ++q) issue_h(0, q);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) issue_w(0, q);
+  if (1 < nk) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue_w(1, q);
+  }
+
   Frag cur, nxt;
-  // One k-step.  On entry stage kt is complete and visible to everybody and `cur` holds its
-  // first k-slice.  The barrier at the top publishes stage kt+1 (each wavefront first waits
-  // for its own 4 loads of it; the 4 of stage kt+2 may stay in flight) and tells that everybody
-  // has left stage kt-1, which is then refilled with k-step kt+3.  Because stage kt+1 is
-  // already visible, its first k-slice is fetched under the last multiplies of stage kt.
-  //
-  // Steady-state form (kt + 3 < nk): no conditionals, so the step is one basic block, and the
-  // fragment reads sit in the middle of a run of multiplies: the compiler cannot see through
-  // the hand-written barrier and load statements and waits for every outstanding LDS read
-  // before the first multiply that follows them, so each batch of reads is issued when the
-  // previous batch has long returned and four multiplies ahead of its first use.
-  auto mfma_pair = [&](const Frag& f, int i) {
 #pragma unroll
-    for (int j = 0; j < TJ; ++j)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
-  };
-  auto step_steady = [&](const bf16x8* st_cur, const bf16x8* st_next, bf16x8* refill) {
-    __builtin_amdgcn_sched_barrier(0);  // the multiplies of the previous step stay in front of the barrier
-    wait_newer<2 * QI>();
-    lds_barrier();
-    mfma_pair(cur, 0);
-    issue_next(refill, 0);
-    mfma_pair(cur, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frag(st_cur, 1, nxt);
-    issue_next(refill, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_pair(cur, 2);
-    issue_next(refill, 2);
-    mfma_pair(cur, 3);
-    issue_next(refill, 3);
+  for (int i = 0; i < 4; ++i) cur.a[i] = bf16x8{};
 #pragma unroll
-    for (int n = 4; n < 2 * QI; ++n) issue_next(refill, n);
+  for (int j = 0; j < 2; ++j) cur.b[j] = bf16x8{};  // "last slice of step -1": multiplies by zero
+
+  // One k-step.  On entry `cur` holds the last slice of the step before.  Outstanding loads of
+  // this wavefront, oldest first: H(kt) [4], W(kt+1) [4]; the barrier needs H(kt) (W(kt) is older).
+  // FULL: kt + 2 < nk, every refill exists and the step is one basic block.
+  auto step = [&](int kt, int sh, int sw, auto full) {
+    constexpr bool FULL = decltype(full)::value;
+    const bf16x8* Hs = ringH + sh * kStage;
+    const bf16x8* Ws = ringW + sw * kStage;
+    const int sh1 = sh ^ 1, sw2 = sw == 0 ? 2 : sw - 1;  // stages of H(kt+1) and W(kt+2)
     __builtin_amdgcn_sched_barrier(0);
-    mfma_pair(nxt, 0);
-    mfma_pair(nxt, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frag(st_next, 0, cur);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_pair(nxt, 2);
-    mfma_pair(nxt, 3);
-  };
-  // General form for the last steps of the k loop (nothing left to refill, no next stage).
-  auto step = [&](const bf16x8* st_cur, const bf16x8* st_next, bf16x8* refill, int kt) {
-    if (kt + 2 < nk) wait_newer<2 * QI>();
+    if (FULL || kt + 1 < nk) wait_newer<4>();
     else wait_newer<0>();
     lds_barrier();
-    read_frag(st_cur, 1, nxt);
+    if (idle) {
+      if (FULL || kt + 1 < nk)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (kt + 3 < nk && i < 2 * QI) issue_one(refill, kt + 3, i);
-      mfma_pair(cur, i);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int q = 0; q < 4; ++q) issue_h(sh1, q);
+      if (FULL || kt + 2 < nk)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) issue_w(sw2, q);
+      return;
     }
-#pragma unroll
-    for (int n = 4; n < 2 * QI; ++n)
-      if (kt + 3 < nk) issue_one(refill, kt + 3, n);
-    if (kt + 1 < nk) read_frag(st_next, 0, cur);
-    mfma_frag(nxt);
+    read_frag(Hs, Ws, 0, nxt);
+    if (FULL || kt + 1 < nk) issue_h(sh1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(cur, 0, 2);
+    if (FULL || kt + 1 < nk) issue_h(sh1, 1);
+    mfma_rows(cur, 2, 4);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frag(Hs, Ws, 1, cur);
+    if (FULL || kt + 1 < nk) issue_h(sh1, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(nxt, 0, 2);
+    if (FULL || kt + 1 < nk) issue_h(sh1, 3);
+    mfma_rows(nxt, 2, 4);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frag(Hs, Ws, 2, nxt);
+    if (FULL || kt + 2 < nk) issue_w(sw2, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(cur, 0, 2);
+    if (FULL || kt + 2 < nk) issue_w(sw2, 1);
+    mfma_rows(cur, 2, 4);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frag(Hs, Ws, 3, cur);
+    if (FULL || kt + 2 < nk) issue_w(sw2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(nxt, 0, 2);
+    if (FULL || kt + 2 < nk) issue_w(sw2, 3);
+    mfma_rows(nxt, 2, 4);
   };
 
-  issue(st0, 0);
-  if (1 < nk) issue(st1, 1);
-  if (2 < nk) issue(st2, 2);
-  if (2 < nk) wait_newer<4 * QI>();
-  else if (1 < nk) wait_newer<2 * QI>();
-  else wait_newer<0>();
-  lds_barrier();
-  if (m0 + wm * 128 >= M) {
-    // None of this wavefront's 128 rows exists (the last row tile of a launch whose M is no
-    // multiple of 256): it keeps its share of the loads and every barrier, in the order of the
-    // steps below, and multiplies nothing.
-    auto idle_step = [&](bf16x8* refill, int kt) {
-      if (kt + 2 < nk) wait_newer<2 * QI>();
-      else wait_newer<0>();
-      lds_barrier();
-      if (kt + 3 < nk) issue(refill, kt + 3);
-    };
-    for (int kt = 0; kt < nk; kt += 4) {
-      idle_step(st3, kt);
-      if (kt + 1 < nk) idle_step(st0, kt + 1);
-      if (kt + 2 < nk) idle_step(st1, kt + 2);
-      if (kt + 3 < nk) idle_step(st2, kt + 3);
-    }
-    return;
+  int kt = 0, sw = 0;
+  for (; kt + 3 < nk; kt += 2) {  // two full steps: kt + 1 + 2 < nk
+    step(kt, 0, sw, std::true_type{});
+    sw = sw == 2 ? 0 : sw + 1;
+    step(kt + 1, 1, sw, std::true_type{});
+    sw = sw == 2 ? 0 : sw + 1;
   }
-  read_frag(st0, 0, cur);
-  int kt = 0;
-  if (6 < nk) {  // the steady loop refills k-step kt + 3: point the loads there
-#pragma unroll
-    for (int n = 0; n < 2 * QI; ++n) gp[n] += 3 * BK;
-    kbase = 3;
+  for (; kt < nk; ++kt) {
+    step(kt, kt & 1, sw, std::false_type{});
+    sw = sw == 2 ? 0 : sw + 1;
   }
-  for (; kt + 6 < nk; kt += 4) {  // all four steps refill: kt + 3 + 3 < nk
-    step_steady(st0, st1, st3);
-    step_steady(st1, st2, st0);
-    step_steady(st2, st3, st1);
-    step_steady(st3, st0, st2);
-    kbase += 4;
-  }
-  for (; kt < nk; kt += 4) {
-    step(st0, st1, st3, kt);
-    if (kt + 1 < nk) step(st1, st2, st0, kt + 1);
-    if (kt + 2 < nk) step(st2, st3, st1, kt + 2);
-    if (kt + 3 < nk) step(st3, st0, st2, kt + 3);
-  }
+  if (idle) return;
+  mfma_rows(cur, 0, 4);  // last slice of the last step
 
-  // Epilogue: logits and per-row (max, sum exp) partials straight from the accumulators.
-  static_assert(TJ == 2, "the epilogue covers 64 tokens per wavefront");
   store_logits_and_partials<4, CE>(a, acc, m0 + wm * 128, n0 + wn * 64, M, lane);
 }
 
@@ -226,9 +195,9 @@ hipError_t launch_head_tiled256(const HeadArgs& a) {
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (a.V + BN - 1) / BN;
   const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
   if (a.labels)
-    FEF_LAUNCH_HEAD((head_tiled256_kernel<2, true>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
+    FEF_LAUNCH_HEAD((head_tiled256_kernel<true>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
   else
-    FEF_LAUNCH_HEAD((head_tiled256_kernel<2, false>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
+    FEF_LAUNCH_HEAD((head_tiled256_kernel<false>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 

@@ -103,6 +103,21 @@ def test_skinny_kernel_two_row_groups(B, K, V):
     assert near == 0
 
 
+@pytest.mark.parametrize("B,K,d,V", [(1, 8, 1024, 3000), (2, 8, 2048, 1500), (1, 16, 2560, 2000), (1, 5, 3072, 1001),
+                                     (2, 4, 3584, 777)])
+def test_skinny_kernel_other_hidden_sizes(B, K, d, V):
+    """Every hidden size the streaming kernels for at most 32 rows are instantiated for (d = 256 KS),
+    with 16 rows or fewer and with 17 to 32; AUTO must pick them."""
+    p = fb.make_params(B, d, V)
+    assert fb.fef_select_gemm(p, K) == fb.FEF_GEMM_SKINNY
+    near = 0
+    for step in range(2):
+        ref, out, st = run_case(B, K, 16, d, V, seed=19, rho=0.8, step=step)
+        near += st["near_flipped"]
+    assert near == 0
+    assert fb.fef_select_gemm(fb.make_params(B, d + 64, V), K) == fb.FEF_GEMM_STREAM     # no instantiation: streaming kernel
+
+
 def test_window_16_batch1_full_size(llada_head):
     """LLaDA-shaped head with a 16-token window at batch 1 (32 rows through the head), every
     output element against the oracle."""
