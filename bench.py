@@ -123,7 +123,7 @@ def acceptance_sweep(args, wl, Wd, dev):
             rows.append({"rho": rho, "tau": tau, "calls": args.sweep, "mean_alpha": a,
                          "mean_committed": float(committed.item()) / args.sweep,
                          "theorem2_at_mean_alpha": ec, "S_ideal": ec / 2.0, "us_per_call": el / args.sweep * 1e6})
-            print("rho %.2f tau %.1f: alpha %.3f  committed %.3f  (1-a^K)/(1-a) %.3f  S %.2f  %.0f us/call"
+            print("rho %.3f tau %.1f: alpha %.3f  committed %.3f  (1-a^K)/(1-a) %.3f  S %.2f  %.0f us/call"
                   % (rho, tau, a, rows[-1]["mean_committed"], ec, ec / 2, rows[-1]["us_per_call"]), file=sys.stderr, flush=True)
     print(json.dumps({"metric": "acceptance sweep of the verify step (mean overlap, committed length, Theorem 2)",
                       "n_gpus": 1, "data": "synthetic", "dtype": wl.dtype,

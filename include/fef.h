@@ -15,7 +15,8 @@
  *               the n_rm committed positions of the pass with the lowest confidence are
  *               re-corrupted through the absorbing forward kernel: each returns to the MASK
  *               state with probability recorrupt_prob (1 by default) and keeps its token
- *               otherwise ("Re-corrupt X^i ~ q(X_t^i | X_0^i)")
+ *               otherwise (the re-corruption line of Algorithm 2, a draw from the forward
+ *               kernel given the predicted clean token)
  *
  * The model forwards that produce the hidden states are outside the library.  The vocabulary
  * head W is shared by both laws (the paper instantiates draft and target with one network).
@@ -31,7 +32,10 @@
  *   - Plain C.  Every data pointer below is a DEVICE pointer owned by the caller unless it
  *     says "host".  fef_params itself lives in host memory.
  *   - The library allocates nothing: scratch space is the caller's `workspace`
- *     (fef_workspace_bytes tells how much).  It keeps no state between calls.
+ *     (fef_workspace_bytes tells how much; fef_verify_step_static uses a buffer built into the
+ *     library instead).  No result depends on an earlier call; the only things the library
+ *     remembers are per-device constants it looks up once (the number of compute units, the
+ *     address of the built-in buffer).
  *   - All work is enqueued on `stream`; the call returns without synchronising and the
  *     outputs are valid in stream order.  Concurrent calls need distinct workspaces.
  *   - Return value: FEF_OK or a negative fef_status.  Arguments are validated on the host
