@@ -66,7 +66,8 @@ def test_gemm_selection(lib):
     assert fb.fef_select_gemm(fb.make_params(3, 4096, 126464), 8) == fb.FEF_GEMM_STREAM
     assert fb.fef_select_gemm(fb.make_params(16, 4096, 126464), 8) == fb.FEF_GEMM_TILED256
     assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_STREAM
-    assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_STREAM
+    assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_SKINNY
+    assert fb.fef_select_gemm(fb.make_params(1, 1088, 1000), 8) == fb.FEF_GEMM_STREAM     # no skinny instantiation for this d
     p = fb.make_params(9, 4096, 126464, gemm_variant=fb.FEF_GEMM_STREAM)
     assert fb.fef_select_gemm(p, 8) == fb.FEF_ERR_UNSUPPORTED
     assert fb.fef_select_gemm(fb.make_params(1, 64, 32, dtype=fb.FEF_F32), 4) == fb.FEF_GEMM_F32
