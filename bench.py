@@ -52,11 +52,13 @@ class HipEvents:
         self.hip.hipEventDestroy(e)
 
 
-def head_bytes(wl, skinny, M):
+def head_bytes(wl, skinny, M, rowstream=False):
     """Algorithmic HBM bytes of one vocabulary-head launch over M rows: W once, H once, fp32
     logits written once, the per-tile (max, sum exp) partials."""
     esz = 2 if wl.dtype == "bf16" else 4
     nT = min(-(-wl.V // 16), 256) if skinny else -(-wl.V // 64)
+    if rowstream:
+        nT = min(256, -(-(-(-wl.V // 16)) // 8))
     return wl.V * wl.d * esz + M * wl.d * esz + M * wl.V * 4 + M * nT * 8
 
 
@@ -220,6 +222,8 @@ def main():
     ap.add_argument("--mfma-leg", default="sweep_b64", metavar="WORKLOAD",
                     help="batched workload of the second timed leg printed under \"mfma\" when the main workload "
                          "is llada_b1 (same head shape); `none` skips it")
+    ap.add_argument("--variant", default="auto", choices=["auto", "skinny", "tiled", "tiled256", "stream", "rowstream"],
+                    help="head kernel (fef_gemm_variant); auto = the library's choice")
     ap.add_argument("--mfma-steps", type=int, default=48, help="timed steps of the second leg")
     ap.add_argument("--event-every", type=int, default=4, metavar="N",
                     help="with inline events, attach them to every N-th timed step (a dispatch with events "
@@ -291,7 +295,10 @@ def time_verify(args, wl, Wd, dev, steps, warmup):
     rounds = [synth.make_round(wl, args.seed, block_index=i // 8, step=i) for i in range(n_rounds)]
     rounds_d = [(hd.to(dev), ht.to(dev)) for hd, ht in rounds]
 
-    vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, dtype=wl.dtype, device=dev)
+    vs = fb.VerifyStep(wl.B, wl.K, wl.block, wl.d, wl.V, dtype=wl.dtype, device=dev,
+                       gemm_variant={"auto": fb.FEF_GEMM_AUTO, "skinny": fb.FEF_GEMM_SKINNY, "tiled": fb.FEF_GEMM_TILED,
+                                     "tiled256": fb.FEF_GEMM_TILED256, "stream": fb.FEF_GEMM_STREAM,
+                                     "rowstream": fb.FEF_GEMM_ROWSTREAM}[args.variant])
     p0 = vs._params()
     p0.phase = fb.FEF_PHASE_DRAFT if args.split else fb.FEF_PHASE_FUSED
     variant = fb.fef_select_gemm(p0, wl.K)
@@ -370,7 +377,7 @@ def time_verify(args, wl, Wd, dev, steps, warmup):
     ms_per_step = elapsed / steps * 1e3
     positions = wl.B * wl.K
     M = positions if args.split else 2 * positions   # rows through one head launch
-    hb = head_bytes(wl, variant == fb.FEF_GEMM_SKINNY, M)
+    hb = head_bytes(wl, variant == fb.FEF_GEMM_SKINNY, M, variant == fb.FEF_GEMM_ROWSTREAM)
     flops = 2.0 * M * wl.V * wl.d
     hbm_time, mfma_time = hb / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if hbm_time >= mfma_time:
@@ -385,6 +392,7 @@ def time_verify(args, wl, Wd, dev, steps, warmup):
                             fb.FEF_GEMM_TILED: "head_tiled_kernel",
                             fb.FEF_GEMM_TILED256: "head_tiled256_kernel",
                             fb.FEF_GEMM_STREAM: "head_stream_kernel",
+                            fb.FEF_GEMM_ROWSTREAM: "head_rowstream_kernel",
                             fb.FEF_GEMM_F32: "head_f32_kernel"}[variant],
                  "avg_kernel_us": head_avg_s * 1e6, "algorithmic_bytes": hb, "flops": flops,
                  "events": "separate" if args.graph else args.events,

@@ -58,7 +58,7 @@ extern "C" {
 
 #define FEF_MAX_K 64
 #define FEF_MAX_BLOCK 4096
-#define FEF_ABI_VERSION 9
+#define FEF_ABI_VERSION 10
 #define FEF_STATIC_SCRATCH_BYTES (32u << 20) /* built-in scratch of fef_verify_step_static        */
 
 typedef enum {
@@ -83,8 +83,14 @@ typedef enum {
   FEF_GEMM_TILED = 2,  /* bf16, any M: plain 128x128 LDS-tiled MFMA GEMM (never picked by AUTO) */
   FEF_GEMM_F32 = 3,    /* f32, any shape: reference-grade FMA kernel                       */
   FEF_GEMM_TILED256 = 4, /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)       */
-  FEF_GEMM_STREAM = 5    /* bf16, M <= 128: all rows x 256 tokens per persistent workgroup, W
-                            streamed through a deep LDS ring (AUTO: 32 < M <= 128)          */
+  FEF_GEMM_STREAM = 5,   /* bf16, M <= 128: all rows x 256 tokens per persistent workgroup, W
+                            streamed through a deep LDS ring (AUTO: 32 < M <= 128 when d is no
+                            multiple of 512; 96 < M <= 128 unless V divides clearly better into
+                            the other kernel's rounds of tiles)                              */
+  FEF_GEMM_ROWSTREAM = 6 /* bf16, M <= 128, d a multiple of 512: every wavefront streams the W rows
+                            of its own 16-token tiles into registers, H through LDS (AUTO:
+                            32 < M <= 96, and 96 < M <= 128 when V divides more than 2 % better
+                            into rounds of 8 x 16 tokens per CU than into rounds of 256)     */
 } fef_gemm_variant;
 
 /* In Algorithm 2 the verification inputs X^(j_m) carry the draft prefix, so a real target

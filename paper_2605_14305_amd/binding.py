@@ -17,10 +17,11 @@ FEF_ERR_WORKSPACE = -3
 FEF_ERR_HIP = -4
 FEF_BF16, FEF_F32 = 0, 1
 FEF_GEMM_AUTO, FEF_GEMM_SKINNY, FEF_GEMM_TILED, FEF_GEMM_F32, FEF_GEMM_TILED256, FEF_GEMM_STREAM = 0, 1, 2, 3, 4, 5
+FEF_GEMM_ROWSTREAM = 6
 FEF_MAX_K, FEF_MAX_BLOCK = 64, 4096
 FEF_PHASE_FUSED, FEF_PHASE_DRAFT, FEF_PHASE_TARGET = 0, 1, 2
 
-ABI_VERSION = 9   # FEF_ABI_VERSION of include/fef.h this binding's fef_params mirrors
+ABI_VERSION = 10   # FEF_ABI_VERSION of include/fef.h this binding's fef_params mirrors
 
 EXPORTS = ["fef_workspace_bytes", "fef_verify_step", "fef_select_gemm", "fef_uniform",
            "fef_status_string", "fef_last_error", "fef_abi_version", "fef_copy_probe", "fef_read_probe",

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfef.so")
-SOURCES = ["fef_api.hip", "head_gemm.hip", "head_gemm_tiled256.hip", "head_gemm_stream.hip",
+SOURCES = ["fef_api.hip", "head_gemm.hip", "head_gemm_tiled256.hip", "head_gemm_stream.hip", "head_gemm_rowstream.hip",
            "verify_kernels.hip", "ce_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -74,7 +74,16 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
   if (v == FEF_GEMM_AUTO) {
     if (p->dtype == FEF_F32) v = FEF_GEMM_F32;
     else if (fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d)) v = FEF_GEMM_SKINNY;
-    else v = M > 128 ? FEF_GEMM_TILED256 : FEF_GEMM_STREAM;
+    else if (M > 128) v = FEF_GEMM_TILED256;
+    else if (!fef::rowstream_supports((int)M, p->d)) v = FEF_GEMM_STREAM;
+    else if (M <= 96) v = FEF_GEMM_ROWSTREAM;  // measured 7 to 8 % ahead of the streaming kernel at M = 48, 64, 96
+    else {
+      // 96 < M <= 128: per token of work the two are within 2 % of each other (streaming kernel ahead), so
+      // what decides is how evenly V divides into each kernel's rounds of tiles (V = 151936: three
+      // rounds of 256 tokens per CU against five of 128)
+      const long st = fef::stream_tokens_per_cu(p->V), rs = fef::rowstream_tokens_per_cu(p->V);
+      v = 100 * st > 102 * rs ? FEF_GEMM_ROWSTREAM : FEF_GEMM_STREAM;
+    }
   }
   switch (v) {
     case FEF_GEMM_SKINNY:
@@ -88,6 +97,10 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
     case FEF_GEMM_STREAM:
       if (p->dtype != FEF_BF16 || !fef::stream_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d))
         return fail(FEF_ERR_UNSUPPORTED, "streaming head kernel needs bf16 and at most 128 rows through the head");
+      break;
+    case FEF_GEMM_ROWSTREAM:
+      if (p->dtype != FEF_BF16 || !fef::rowstream_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d))
+        return fail(FEF_ERR_UNSUPPORTED, "row-streaming head kernel needs bf16, at most 128 rows through the head and d a multiple of 512");
       break;
     case FEF_GEMM_F32:
       if (p->dtype != FEF_F32) return fail(FEF_ERR_UNSUPPORTED, "f32 head kernel needs dtype f32");
@@ -111,6 +124,11 @@ fef_status make_layout(const fef_params* p, int32_t K, int32_t block, Layout* L)
     L->tile_unit = fef::kSkinnyUnit;
     L->tile_T = (p->V + fef::kSkinnyUnit - 1) / fef::kSkinnyUnit;
     L->nT = L->tile_T < fef::kSkinnyMaxGrid ? L->tile_T : fef::kSkinnyMaxGrid;
+  } else if (L->variant == FEF_GEMM_ROWSTREAM) {
+    // as above, with this kernel's grid
+    L->tile_unit = fef::kSkinnyUnit;
+    L->tile_T = (p->V + fef::kSkinnyUnit - 1) / fef::kSkinnyUnit;
+    L->nT = fef::rowstream_grid(p->V);
   } else {
     L->tile_unit = fef::kTiledTn;
     L->tile_T = L->nT = (p->V + fef::kTiledTn - 1) / fef::kTiledTn;
@@ -308,6 +326,7 @@ fef_status run_step(const fef_params* prm, int phase, int n_transfer, const void
     case FEF_GEMM_TILED: e = fef::launch_head_tiled(h); break;
     case FEF_GEMM_TILED256: e = fef::launch_head_tiled256(h); break;
     case FEF_GEMM_STREAM: e = fef::launch_head_stream(h); break;
+    case FEF_GEMM_ROWSTREAM: e = fef::launch_head_rowstream(h); break;
     default: e = fef::launch_head_f32(h); break;
   }
   if (e != hipSuccess) return fail(FEF_ERR_HIP, "head kernel launch: %s", hipGetErrorString(e));

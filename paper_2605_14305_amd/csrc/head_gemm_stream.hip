@@ -254,6 +254,11 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
 
 bool stream_supports(int M, int d) { return M <= SM && d % 64 == 0; }
 
+int stream_tokens_per_cu(int V) {
+  const int n_tiles = (V + SN - 1) / SN;
+  return (n_tiles + kSkinnyMaxGrid - 1) / kSkinnyMaxGrid * SN;
+}
+
 template <int NI>
 static void launch_stream(const HeadArgs& a, int grid, int n_tiles) {
   if (a.labels) FEF_LAUNCH_HEAD((head_stream_kernel<NI, true>), dim3((unsigned)grid), dim3(512), a, a, n_tiles);

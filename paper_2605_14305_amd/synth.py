@@ -51,7 +51,11 @@ WORKLOADS = {
                           dtype="bf16", rho=0.9, logit_std=3.0),
     "llada_b2": Workload("llada_b2", B=2, K=8, block=32, gen_len=256, d=4096, V=126464,
                          dtype="bf16", rho=0.9, logit_std=3.0),
+    "llada_b3": Workload("llada_b3", B=3, K=8, block=32, gen_len=256, d=4096, V=126464,
+                         dtype="bf16", rho=0.9, logit_std=3.0),
     "llada_b4": Workload("llada_b4", B=4, K=8, block=32, gen_len=256, d=4096, V=126464,
+                         dtype="bf16", rho=0.9, logit_std=3.0),
+    "llada_b6": Workload("llada_b6", B=6, K=8, block=32, gen_len=256, d=4096, V=126464,
                          dtype="bf16", rho=0.9, logit_std=3.0),
     "llada_b8": Workload("llada_b8", B=8, K=8, block=32, gen_len=256, d=4096, V=126464,
                          dtype="bf16", rho=0.9, logit_std=3.0),

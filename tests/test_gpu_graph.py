@@ -13,7 +13,8 @@ DEV = "cuda"
 
 @pytest.mark.parametrize("B,K,d,V,variant", [(1, 8, 512, 5000, fb.FEF_GEMM_SKINNY), (6, 4, 128, 1000, fb.FEF_GEMM_TILED),
                                               (40, 4, 64, 700, fb.FEF_GEMM_TILED256),
-                                              (6, 8, 256, 3000, fb.FEF_GEMM_STREAM), (3, 8, 512, 900, fb.FEF_GEMM_STREAM)])
+                                              (6, 8, 256, 3000, fb.FEF_GEMM_STREAM), (3, 8, 512, 900, fb.FEF_GEMM_STREAM),
+                                              (3, 8, 512, 9000, fb.FEF_GEMM_ROWSTREAM)])
 def test_graph_replays_match_eager(B, K, d, V, variant):
     block = 16
     W = synth.make_head(V, d, 3).to(DEV)

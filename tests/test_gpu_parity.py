@@ -162,14 +162,35 @@ def test_stream_kernel_small_shapes(B, K, d, V):
     assert st["near_flipped"] <= B // 20
 
 
-@pytest.mark.parametrize("B", [4, 8])
-def test_llada_shape_through_the_streaming_kernel(llada_head, B):
-    """B=4 and B=8 at full d and V (64 and 128 rows through the head, the two tile heights): the
-    configurations AUTO gives the streaming kernel; the oracle checks a seeded subset of sequences."""
+@pytest.mark.parametrize("B,K,d,V", [(5, 8, 512, 1000), (4, 5, 512, 777), (8, 8, 512, 2050), (17, 1, 512, 1),
+                                     (4, 16, 1024, 300), (2, 9, 3584, 1500), (6, 8, 1024, 513), (7, 8, 512, 2049),
+                                     (3, 16, 512, 40000), (5, 8, 1536, 33000), (2, 16, 512, 16 * 2048 + 5)])
+def test_rowstream_kernel_small_shapes(B, K, d, V):
+    """The kernel that streams W into registers (33 to 128 rows, d a multiple of 512): the three
+    stage heights (64, 96, 128 rows), one to seven macro-steps rounds per tile, fewer tiles than
+    wavefronts (empty runs), runs of unequal length inside a workgroup, ragged last tile."""
+    assert fb.fef_select_gemm(fb.make_params(B, d, V), K) == fb.FEF_GEMM_ROWSTREAM
+    flipped = 0
+    for step in range(2):
+        ref, out, st = run_case(B, K, max(K, 16), d, V, seed=23, rho=0.8, step=step, variant=fb.FEF_GEMM_ROWSTREAM)
+        flipped += st["near_flipped"]
+    assert flipped <= max(1, B // 10)
+    ref, out, st = run_case(B, K, max(K, 16), d, V, seed=23, rho=0.9, step=4, variant=fb.FEF_GEMM_ROWSTREAM, greedy=True,
+                            temperature=0.7)
+    assert st["near_flipped"] <= max(1, B // 10)
+
+
+@pytest.mark.parametrize("B,variant", [(4, fb.FEF_GEMM_AUTO), (6, fb.FEF_GEMM_AUTO), (8, fb.FEF_GEMM_AUTO),
+                                       (8, fb.FEF_GEMM_ROWSTREAM), (4, fb.FEF_GEMM_STREAM)])
+def test_llada_shape_through_the_streaming_kernels(llada_head, B, variant):
+    """B = 4, 6, 8 at full d and V (64, 96, 128 rows through the head): AUTO gives the first two to
+    the row-streaming kernel and the third to the LDS-streaming one; each kernel also on the size
+    AUTO gives the other.  The oracle checks a seeded subset of sequences."""
     wl, W, Wd, W64 = llada_head
     K, block = 8, 32
-    vs = fb.VerifyStep(B, K, block, wl.d, wl.V, device=DEV, diag=True)
-    assert fb.fef_select_gemm(vs._params(), K) == fb.FEF_GEMM_STREAM
+    vs = fb.VerifyStep(B, K, block, wl.d, wl.V, device=DEV, diag=True, gemm_variant=variant)
+    want = {fb.FEF_GEMM_AUTO: fb.FEF_GEMM_ROWSTREAM if B <= 6 else fb.FEF_GEMM_STREAM}.get(variant, variant)
+    assert fb.fef_select_gemm(vs._params(), K) == want
     hd, ht = synth.make_hidden(B, K, wl.d, 9, wl.rho, wl.sigma_h, "bf16", 0, 2)
     tok, acc, rem = vs(hd.to(DEV), ht.to(DEV), Wd, 9, step=2)
     torch.cuda.synchronize()
@@ -239,7 +260,7 @@ def test_skinny_and_tiled_agree():
 def test_deterministic_bits():
     W = synth.make_head(5000, 512, 1).to(DEV)
     hd, ht = (t.to(DEV) for t in synth.make_hidden(2, 4, 512, 1, 0.8, 3.0 / (0.02 * np.sqrt(512))))
-    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED, fb.FEF_GEMM_TILED256, fb.FEF_GEMM_STREAM):
+    for variant in (fb.FEF_GEMM_SKINNY, fb.FEF_GEMM_TILED, fb.FEF_GEMM_TILED256, fb.FEF_GEMM_STREAM, fb.FEF_GEMM_ROWSTREAM):
         outs = []
         for rep in range(3):
             vs = fb.VerifyStep(2, 4, 8, 512, 5000, diag=True, diag_logits=True, gemm_variant=variant)
