@@ -15,6 +15,8 @@
 //   head_tiled_kernel   any M.  128x128x64 LDS-tiled MFMA GEMM, XCD-aware tile order so the
 //                       workgroups that share a W tile run on the same L2.
 //   head_f32_kernel     fp32 inputs, plain FMA; tiny instances only.
+#include <type_traits>
+
 #include "head_common.hpp"
 
 namespace fef {
@@ -100,16 +102,61 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny_kernel(HeadArgs a,
   // running (max, sum exp) over this thread's tiles, replicated over the item's 4 lanes
   float run_m = -INFINITY, run_s = 0.f;
 
-  bf16x8 buf0[KS], buf1[KS];
+  // W prefetch.  The order and grouping of a wavefront's loads decide the rate of the whole kernel;
+  // what follows was found with a read-only kernel of this access pattern and confirmed here.
+  // (1) Loads go out in bursts of about 8 (of 1 KB each): a read-only kernel gets 6.4 to 6.6 TB/s with
+  // bursts of 8, 6.2 with 4 and 5.9 with 16, and one load after each multiply is slower than any of
+  // these.  So a tile of 10 or more k-steps is fetched as two halves, each requested again as soon
+  // as it has been multiplied; shorter tiles are fetched whole, one tile ahead, into two buffers.
+  // (2) Inside a burst the LAST 64-byte piece of the half goes first, then the others in ascending
+  // order: 4 to 5 % faster than ascending order throughout (165 against 169 us at d = 4096, V =
+  // 126464); any order that touches both 256-byte blocks of the half within its first two loads
+  // does as well, strictly alternating ones do not.
+  // (3) No tile is fetched or multiplied twice to make the loop uniform: one extra tile per workgroup
+  // (a thirtieth of its work) costs its full time although it hits in cache.
+  constexpr bool kHalves = KS >= 10;
+  constexpr int GA = kHalves ? KS / 2 : KS, GB = kHalves ? KS - GA : KS;
+  bf16x8 buf0[GA], buf1[GB];
+  auto load_half = [&](int t, auto half, auto& buf) {
+    constexpr int H = decltype(half)::value;
+    constexpr int G = H ? GB : GA;
+    const int v = min(t * 16 + i16, a.V - 1);
+    const __bf16* wp = Wl + (size_t)v * a.d + 32 * (H * GA);
+    buf[G - 1] = *reinterpret_cast<const bf16x8*>(wp + 32 * (G - 1));
+    asm volatile("" ::: "memory");  // keeps the order of the requests
+#pragma unroll
+    for (int s = 0; s < G - 1; ++s) {
+      buf[s] = *reinterpret_cast<const bf16x8*>(wp + 32 * s);
+      asm volatile("" ::: "memory");
+    }
+  };
+  using Half0 = std::integral_constant<int, 0>;
+  using Half1 = std::integral_constant<int, 1>;
   floatx4 acc[NB];
   int par = 0;
   int tflush = t0;  // first tile whose logits are still staged in LDS
-  if (t0 < t1) load_tile(t0, buf0);
+  if (t0 < t1) {
+    if constexpr (kHalves) {
+      load_half(t0, Half0{}, buf0);
+      load_half(t0, Half1{}, buf1);
+    } else {
+      load_tile(t0, buf0);
+    }
+  }
   for (int t = t0; t < t1; t += NB) {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       if (t + i < t1) {
-        if (i & 1) {
+        if constexpr (kHalves) {
+          floatx4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s = 0; s < GA; ++s) c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf0[s], hreg[s], c, 0, 0, 0);
+          if (t + i + 1 < t1) load_half(t + i + 1, Half0{}, buf0);
+#pragma unroll
+          for (int s = 0; s < GB; ++s) c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf1[s], hreg[GA + s], c, 0, 0, 0);
+          if (t + i + 1 < t1) load_half(t + i + 1, Half1{}, buf1);
+          acc[i] = c;
+        } else if (i & 1) {
           if (t + i + 1 < t1) load_tile(t + i + 1, buf0);
           acc[i] = mfma_tile(buf1);
         } else {
@@ -214,12 +261,24 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny32_kernel(HeadArgs 
   const int t1 = (int)((long)(blockIdx.x + 1) * tiles_total / gridDim.x);
   const __bf16* Wl = (const __bf16*)a.W + kofs;
 
+  // One W buffer of KS registers, refilled in two halves (tiles of 10 or more k-steps): a half is
+  // requested again, as one burst with its last piece first, as soon as its multiplies are done
+  // (see the kernel for M <= 16 for what the grouping and the order are worth).
+  constexpr bool kHalves = KS >= 10;
+  constexpr int GA = kHalves ? KS / 2 : KS;
   bf16x8 buf[KS];
-  auto load_tile = [&](int t) {
+  auto load_part = [&](int t, int s0, int s1) {
     const int v = min(t * 16 + i16, a.V - 1);
     const __bf16* wp = Wl + (size_t)v * a.d;
+    if (kHalves) {  // a burst: its last piece first
+      buf[s1 - 1] = *reinterpret_cast<const bf16x8*>(wp + 32 * (s1 - 1));
+      asm volatile("" ::: "memory");
+    }
 #pragma unroll
-    for (int s = 0; s < KS; ++s) buf[s] = *reinterpret_cast<const bf16x8*>(wp + 32 * s);
+    for (int s = s0; s < s1 - (kHalves ? 1 : 0); ++s) {
+      buf[s] = *reinterpret_cast<const bf16x8*>(wp + 32 * s);
+      asm volatile("" ::: "memory");
+    }
   };
 
   // Reduction item of this thread inside a batch: tile jt_o, row group mt_o, row m of it,
@@ -231,20 +290,28 @@ __global__ __launch_bounds__(kSkinnyThreads) void head_skinny32_kernel(HeadArgs 
 
   floatx4 acc[NB][2];
   int tflush = t0;
-  if (t0 < t1) load_tile(t0);
+  if (t0 < t1) load_part(t0, 0, KS);
   for (int t = t0; t < t1; t += NB) {
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
       if (t + i < t1) {
         floatx4 c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
+        for (int s = 0; s < GA; ++s) {
           c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[s], hreg[0][s], c0, 0, 0, 0);
           c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[s], hreg[1][s], c1, 0, 0, 0);
         }
+        if (t + i + 1 < t1) load_part(t + i + 1, 0, GA);
+        if constexpr (kHalves) {
+#pragma unroll
+          for (int s = GA; s < KS; ++s) {
+            c0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[s], hreg[0][s], c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[s], hreg[1][s], c1, 0, 0, 0);
+          }
+          if (t + i + 1 < t1) load_part(t + i + 1, GA, KS);
+        }
         acc[i][0] = c0;
         acc[i][1] = c1;
-        if (t + i + 1 < t1) load_tile(t + i + 1);
       }
     }
     const int nb = min(NB, t1 - t);
