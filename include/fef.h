@@ -89,7 +89,7 @@ typedef enum {
                             the other kernel's rounds of tiles)                              */
   FEF_GEMM_ROWSTREAM = 6 /* bf16, M <= 128, d a multiple of 512: every wavefront streams the W rows
                             of its own 16-token tiles into registers, H through LDS (AUTO:
-                            32 < M <= 96, and 96 < M <= 128 when V divides more than 2 % better
+                            32 < M <= 96, and 96 < M <= 128 when V divides more than 9 % better
                             into rounds of 8 x 16 tokens per CU than into rounds of 256)     */
 } fef_gemm_variant;
 

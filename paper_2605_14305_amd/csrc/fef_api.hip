@@ -78,11 +78,11 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
     else if (!fef::rowstream_supports((int)M, p->d)) v = FEF_GEMM_STREAM;
     else if (M <= 96) v = FEF_GEMM_ROWSTREAM;  // measured 7 to 8 % ahead of the streaming kernel at M = 48, 64, 96
     else {
-      // 96 < M <= 128: per token of work the two are within 2 % of each other (streaming kernel ahead), so
-      // what decides is how evenly V divides into each kernel's rounds of tiles (V = 151936: three
-      // rounds of 256 tokens per CU against five of 128)
+      // 96 < M <= 128: per token of work the streaming kernel is 9 % ahead (221 against 240 us at d = 4096,
+      // V = 126464), unless V divides that much better into the other kernel's rounds of tiles
+      // (V = 151936: three rounds of 256 tokens per CU against five of 128; measured 281 against 274 us)
       const long st = fef::stream_tokens_per_cu(p->V), rs = fef::rowstream_tokens_per_cu(p->V);
-      v = 100 * st > 102 * rs ? FEF_GEMM_ROWSTREAM : FEF_GEMM_STREAM;
+      v = 100 * st > 109 * rs ? FEF_GEMM_ROWSTREAM : FEF_GEMM_STREAM;
     }
   }
   switch (v) {

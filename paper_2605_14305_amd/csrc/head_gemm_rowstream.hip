@@ -32,6 +32,13 @@
 // registers it releases (the wait statement takes them as in/out operands), so the multiplies
 // cannot move above it.  Wavefronts whose run is shorter than the workgroup's longest keep issuing
 // loads (of an address that hits in cache) so that the counts hold for everybody.
+//
+// The compiler takes a value loaded this way to exist from the load statement on.  That is sound as
+// long as it never copies such a value before the wait, i.e. as long as every multiply reads its W
+// operand from the very registers a load statement wrote; the build checks the generated assembly
+// for exactly this and fails otherwise.  (The kernels for M <= 32 show what happens when it does
+// not hold: there, loop-carried buffers filled by assembly loads were shuffled at the loop head,
+// before their wait; they use plain loads, which the compiler counts itself.)
 #include <type_traits>
 
 #include "head_common.hpp"
