@@ -188,16 +188,178 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
   store_logits_and_partials<4, CE>(a, acc, m0 + wm * 128, n0 + wn * 64, M, lane);
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// The same tile with FOUR wavefronts in a 2 x 2 grid, each 128 x 128 as 4 x 4 MFMA tiles (256
+// accumulator registers; one wavefront per SIMD has 512 registers to itself), for M > 256.
+//
+// Why: with eight wavefronts of 128 x 64, a 16-wide slice of k costs every wavefront 4 + 2 fragment
+// reads of 1 KB for 8 multiplies, 48 KB per CU and slice, which together with the 16 KB the loads
+// deposit per slice is all the LDS can move (128 bytes per clock) in the 512 clocks the multiplies
+// of a slice take: the matrix units cannot be busier than the LDS lets them.  A 128 x 128
+// wavefront reads 4 + 4 fragments for 16 multiplies: 32 KB per CU and slice, three quarters of
+// the LDS rate.  (At M = 256 the kernel is short of memory parallelism rather than of LDS rate and
+// the eight wavefronts do better.)
+//
+// Loads: wavefront w fills rows [64 w, 64 w + 64) of an H stage and of a W stage (8 + 8
+// instructions per k-step, four per slice).
+//
+// One workgroup per tile, as above.  A persistent form (one workgroup per CU walking the tiles
+// b, b + G, ... and asking for the first stages of its next tile before the epilogue of the current
+// one) was measured 2.5 % slower at M = 512 to 2048: the hardware's dispatch of one workgroup per
+// tile balances the CUs better than a fixed share of 15 or 16 tiles each.
+// ---------------------------------------------------------------------------------------------
+template <bool CE>
+__global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_tiles, int n_tiles) {
+  __shared__ bf16x8 ringH[kRingH * kStage];  // 64 KB
+  __shared__ bf16x8 ringW[kRingW * kStage];  // 96 KB
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int j32 = lane & 31, h = lane >> 5;
+  const int M = a.nrows;
+  const int nk = a.d / BK;
+
+  const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  const int nt = xcd + 8 * (seq / m_tiles), mt = seq % m_tiles;
+  if (nt >= n_tiles) return;
+  const int m0 = mt * BM, n0 = nt * BN;
+
+  const __bf16* gh[8];
+  const __bf16* gw[8];
+  const uint32_t slotH = lds_offset(ringH + wave * 64 * 8), slotW = lds_offset(ringW + wave * 64 * 8);
+  constexpr uint32_t kStageBytes = kStage * 16;
+  auto issue_h = [&](int stage, int q) {
+    load_to_lds_16(gh[q], slotH + stage * kStageBytes + q * 1024);
+    gh[q] += BK;
+  };
+  auto issue_w = [&](int stage, int q) {
+    load_to_lds_16(gw[q], slotW + stage * kStageBytes + q * 1024);
+    gw[q] += BK;
+  };
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int rl = wave * 64 + q * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((rl >> 1) & 7);
+    const int r = min(m0 + rl, M - 1);      // rows past M / V re-read the last row; masked in the epilogue
+    const int v = min(n0 + rl, a.V - 1);
+    gh[q] = h_row(a, r) + c * 8;
+    gw[q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
+  }
+  // prologue: H(0), W(0), W(1)
+#pragma unroll
+  for (int q = 0; q < 8; ++q) issue_h(0, q);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) issue_w(0, q);
+  if (1 < nk) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue_w(1, q);
+  }
+
+  floatx16 acc[2][4][2];  // [64-token half][32-row tile][32-token tile]
+  struct Frag { bf16x8 a[4], b[4]; };
+  auto read_frag = [&](const bf16x8* Hs, const bf16x8* Ws, int ks, Frag& f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f.a[i] = Hs[swz(wm * 128 + i * 32 + j32, ks * 2 + h)];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) f.b[j] = Ws[swz(wn * 128 + j * 32 + j32, ks * 2 + h)];
+  };
+  auto mfma_row = [&](const Frag& f, int i) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      acc[j >> 1][i][j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[j >> 1][i][j & 1], 0, 0, 0);
+  };
+
+  const bool idle = m0 + wm * 128 >= M;  // none of this wavefront's rows exists: loads and barriers only
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[c][i][j] = floatx16{};
+  Frag cur, nxt;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) cur.a[i] = cur.b[i] = bf16x8{};  // "last slice of step -1": multiplies by zero
+
+  // One k-step; outstanding loads of this wavefront on entry, oldest first: H(kt) [8], W(kt+1) [8].
+  auto step = [&](int kt, int sh, int sw, auto full) {
+    constexpr bool FULL = decltype(full)::value;
+    const bf16x8* Hs = ringH + sh * kStage;
+    const bf16x8* Ws = ringW + sw * kStage;
+    const int sh1 = sh ^ 1, sw2 = sw == 0 ? 2 : sw - 1;
+    const bool more_h = FULL || kt + 1 < nk, more_w = FULL || kt + 2 < nk;
+    __builtin_amdgcn_sched_barrier(0);
+    if (more_h) wait_newer<8>();
+    else wait_newer<0>();
+    lds_barrier();
+    if (idle) {
+      if (more_h)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) issue_h(sh1, q);
+      if (more_w)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) issue_w(sw2, q);
+      return;
+    }
+    // slice s of this step is read while slice s - 1 (s = 0: the last slice of the step before) is
+    // multiplied; one load goes out after each row of four multiplies
+    auto phase = [&](int ks, Frag& rd, const Frag& mm, bool h_loads, int q0) {
+      read_frag(Hs, Ws, ks, rd);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        mfma_row(mm, i);
+        if (h_loads) {
+          if (more_h) issue_h(sh1, q0 + i);
+        } else {
+          if (more_w) issue_w(sw2, q0 + i);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    phase(0, nxt, cur, true, 0);
+    phase(1, cur, nxt, true, 4);
+    phase(2, nxt, cur, false, 0);
+    phase(3, cur, nxt, false, 4);
+  };
+
+  int kt = 0, sw = 0;
+  for (; kt + 3 < nk; kt += 2) {  // two full steps: kt + 1 + 2 < nk
+    step(kt, 0, sw, std::true_type{});
+    sw = sw == 2 ? 0 : sw + 1;
+    step(kt + 1, 1, sw, std::true_type{});
+    sw = sw == 2 ? 0 : sw + 1;
+  }
+  for (; kt < nk; ++kt) {
+    step(kt, kt & 1, sw, std::false_type{});
+    sw = sw == 2 ? 0 : sw + 1;
+  }
+  if (idle) return;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) mfma_row(cur, i);  // last slice of the last step
+
+  store_logits_and_partials<4, CE>(a, acc[0], m0 + wm * 128, n0 + wn * 128, M, lane);
+  store_logits_and_partials<4, CE>(a, acc[1], m0 + wm * 128, n0 + wn * 128 + 64, M, lane);
+}
+
 }  // namespace
 
 hipError_t launch_head_tiled256(const HeadArgs& a) {
   const int M = a.nrows;
   const int m_tiles = (M + BM - 1) / BM, n_tiles = (a.V + BN - 1) / BN;
   const long grid = 8L * ((n_tiles + 7) / 8) * m_tiles;
+  if (m_tiles == 1) {  // M <= 256: eight wavefronts of 128 x 64, one workgroup per tile
+    if (a.labels)
+      FEF_LAUNCH_HEAD((head_tiled256_kernel<true>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
+    else
+      FEF_LAUNCH_HEAD((head_tiled256_kernel<false>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
+    return hipGetLastError();
+  }
+  // M > 256: four wavefronts of 128 x 128
   if (a.labels)
-    FEF_LAUNCH_HEAD((head_tiled256_kernel<true>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
+    FEF_LAUNCH_HEAD((head_tiled256w4_kernel<true>), dim3((unsigned)grid), dim3(256), a, a, m_tiles, n_tiles);
   else
-    FEF_LAUNCH_HEAD((head_tiled256_kernel<false>), dim3((unsigned)grid), dim3(512), a, a, m_tiles, n_tiles);
+    FEF_LAUNCH_HEAD((head_tiled256w4_kernel<false>), dim3((unsigned)grid), dim3(256), a, a, m_tiles, n_tiles);
   return hipGetLastError();
 }
 

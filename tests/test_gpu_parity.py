@@ -145,8 +145,10 @@ def test_tiled_kernel_small_shapes(B, K, d, V):
 
 
 @pytest.mark.parametrize("B,K,d,V", [(5, 8, 64, 1000), (20, 8, 512, 777), (40, 4, 128, 2050), (1, 1, 64, 1),
-                                     (17, 16, 256, 300)])
+                                     (17, 16, 256, 300), (32, 8, 192, 515), (70, 8, 128, 520)])
 def test_tiled256_kernel_small_shapes(B, K, d, V):
+    """Up to 256 rows: eight wavefronts of 128 x 64; above: four of 128 x 128 (320 and 544 rows: a last
+    row tile with wavefronts that have no rows; 512: two full row tiles; 1120: five)."""
     ref, out, st = run_case(B, K, max(K, 16), d, V, seed=13, rho=0.8, variant=fb.FEF_GEMM_TILED256)
     assert st["near_flipped"] <= B // 20
 
