@@ -169,7 +169,7 @@ def bench_cross_entropy(args, wl, W, Wd, dev):
         ach = flops / head_s / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
-    roof.update({"kernel": "head_stream_kernel" if R <= 128 else "head_tiled256_kernel",
+    roof.update({"kernel": "head_stream_kernel" if R <= 128 else ("head_tiled256_kernel" if R <= 256 else "head_tiled256w4_kernel"),
                  "avg_kernel_us": head_s * 1e6, "algorithmic_bytes": hb, "flops": flops, "events": "inline"})
     out = {"metric": "cross-entropy rows/s through the vocabulary head (forward, no logits written)",
            "value": R / (elapsed / args.steps), "unit": "rows/s", "n_gpus": 1, "steps": args.steps,
@@ -390,7 +390,7 @@ def time_verify(args, wl, Wd, dev, steps, warmup):
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
     roof.update({"kernel": {fb.FEF_GEMM_SKINNY: "head_skinny_kernel" if M <= 16 else "head_skinny32_kernel",
                             fb.FEF_GEMM_TILED: "head_tiled_kernel",
-                            fb.FEF_GEMM_TILED256: "head_tiled256_kernel",
+                            fb.FEF_GEMM_TILED256: "head_tiled256_kernel" if M <= 256 else "head_tiled256w4_kernel",
                             fb.FEF_GEMM_STREAM: "head_stream_kernel",
                             fb.FEF_GEMM_ROWSTREAM: "head_rowstream_kernel",
                             fb.FEF_GEMM_F32: "head_f32_kernel"}[variant],

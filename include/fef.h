@@ -258,8 +258,9 @@ float fef_uniform(uint64_t seed, uint32_t position, uint32_t step, uint32_t sequ
 fef_status fef_copy_probe(void* dst, const void* src, size_t nbytes, void* stream);
 
 /* Measurement aid, not part of the verify path: read nbytes (a multiple of 16) at src (device,
- * 16-byte aligned) once, contiguously, with nothing else to do: the streaming-read rate this
- * gives is the practical ceiling the HBM-bound head kernels are compared with.  `sink` (device,
+ * 16-byte aligned) once with nothing else to do, in the fastest access pattern found for this
+ * machine (128 KB blocks read as 16 rows of 8 KB in bursts of eight 16-byte loads per lane): the
+ * rate this gives is the practical ceiling the HBM-bound head kernels are compared with.  `sink` (device,
  * 4 bytes, caller-owned) exists so that the reads have a use; it is written only if the XOR of
  * all words equals one particular value.  Asynchronous on `stream`. */
 fef_status fef_read_probe(const void* src, size_t nbytes, void* sink, void* stream);

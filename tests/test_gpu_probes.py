@@ -26,6 +26,22 @@ def test_read_probe_reads_in_bounds_and_leaves_the_sink_alone():
         assert int(sink.item()) == 0
 
 
+def test_read_probe_reads_every_word_once():
+    """The sink is written iff some thread's words XOR to one particular value: plant that value in one
+    word of an otherwise zero buffer (inside the 128 KB blocks, at their edges, in the linear tail) and
+    the sink must be set, which it is only if that word was read an odd number of times."""
+    n = 5 * (1 << 15) * 7 + 4 * 1237          # 35 blocks of 128 KB and a tail of 4948 words
+    magic = 0x9E3779B9 - (1 << 32)
+    for pos in (0, 1, 12345, (1 << 15) - 1, 1 << 15, 17 * (1 << 15) + 511 * 4, 35 * (1 << 15) - 1, 35 * (1 << 15),
+                n - 5, n - 1):
+        src = torch.zeros(n, dtype=torch.int32, device=DEV)
+        src[pos] = magic
+        sink = torch.zeros(1, dtype=torch.int32, device=DEV)
+        fb.fef_read_probe(src, sink)
+        torch.cuda.synchronize()
+        assert int(sink.item()) == 1, pos
+
+
 def test_probes_reject_bad_arguments():
     src = torch.zeros(8, dtype=torch.int32, device=DEV)
     sink = torch.zeros(1, dtype=torch.int32, device=DEV)
