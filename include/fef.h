@@ -84,13 +84,12 @@ typedef enum {
   FEF_GEMM_F32 = 3,    /* f32, any shape: reference-grade FMA kernel                       */
   FEF_GEMM_TILED256 = 4, /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)       */
   FEF_GEMM_STREAM = 5,   /* bf16, M <= 128: all rows x 256 tokens per persistent workgroup, W
-                            streamed through a deep LDS ring (AUTO: 32 < M <= 128 when d is no
-                            multiple of 512; 96 < M <= 128 unless V divides clearly better into
-                            the other kernel's rounds of tiles)                              */
+                            streamed through a deep LDS ring, 64- or 128-row tiles (AUTO: 32 < M <= 128
+                            where the other streaming kernel is not chosen)                  */
   FEF_GEMM_ROWSTREAM = 6 /* bf16, M <= 128, d a multiple of 512: every wavefront streams the W rows
-                            of its own 16-token tiles into registers, H through LDS (AUTO:
-                            32 < M <= 96, and 96 < M <= 128 when V divides more than 9 % better
-                            into rounds of 8 x 16 tokens per CU than into rounds of 256)     */
+                            of its own 16-token tiles into registers, H through LDS, 64-, 96- or
+                            128-row tiles (AUTO: 32 < M <= 48 and 64 < M <= 96, where it needs
+                            fewer rows than the kernel above)                                */
 } fef_gemm_variant;
 
 /* In Algorithm 2 the verification inputs X^(j_m) carry the draft prefix, so a real target

@@ -76,13 +76,15 @@ fef_status select_variant(const fef_params* p, int32_t K, int* variant) {
     else if (fef::skinny_supports((int)(M > 1 << 20 ? 1 << 20 : M), p->d)) v = FEF_GEMM_SKINNY;
     else if (M > 128) v = FEF_GEMM_TILED256;
     else if (!fef::rowstream_supports((int)M, p->d)) v = FEF_GEMM_STREAM;
-    else if (M <= 96) v = FEF_GEMM_ROWSTREAM;  // measured 7 to 8 % ahead of the streaming kernel at M = 48, 64, 96
-    else {
-      // 96 < M <= 128: per token of work the streaming kernel is 9 % ahead (221 against 240 us at d = 4096,
-      // V = 126464), unless V divides that much better into the other kernel's rounds of tiles
-      // (V = 151936: three rounds of 256 tokens per CU against five of 128; measured 281 against 274 us)
-      const long st = fef::stream_tokens_per_cu(p->V), rs = fef::rowstream_tokens_per_cu(p->V);
-      v = 100 * st > 109 * rs ? FEF_GEMM_ROWSTREAM : FEF_GEMM_STREAM;
+    else if (M <= 48 || (M > 64 && M <= 96)) {
+      // the row-streaming kernel works on 64, 96 or 128 rows, the LDS-streaming one on 64 or 128: where the
+      // first needs fewer it is ahead (whole step at d = 4096, V = 126464: 219 against 222 us at M = 48, 253
+      // against 266 at M = 96), where both need the same the second is (219.5 against 224 us at M = 64)
+      v = FEF_GEMM_ROWSTREAM;
+    } else {
+      // 48 < M <= 64 and 96 < M <= 128 (216 against 242 us at M = 128; also at V = 151936, which divides
+      // better into the other kernel's rounds of tiles: 272 against 275 us)
+      v = FEF_GEMM_STREAM;
     }
   }
   switch (v) {

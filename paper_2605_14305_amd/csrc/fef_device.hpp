@@ -78,10 +78,6 @@ bool stream_supports(int M, int d);
 hipError_t launch_head_stream(const HeadArgs& a);
 bool rowstream_supports(int M, int d);
 int rowstream_grid(int V);  // workgroups = partial slots per row
-// Tokens the busiest workgroup multiplies when the kernel runs one workgroup on each of 256 CUs:
-// its rounds of tiles times the tokens of a round.
-int stream_tokens_per_cu(int V);
-int rowstream_tokens_per_cu(int V);
 hipError_t launch_head_rowstream(const HeadArgs& a);
 hipError_t launch_head_f32(const HeadArgs& a);
 

@@ -106,6 +106,8 @@ __global__ __launch_bounds__(512) void head_rowstream_kernel(HeadArgs a, int til
   // workgroup starts its walk at another macro-step and wraps round (H and W alike).
   const int km0 = (int)((blockIdx.x * 37u) % (unsigned)nkm);
   int h_km = km0;  // macro-step (within a tile) of the next H stage to request
+  // (one write of M0 for the HQ loads of a stage, with the loads told apart by their instruction offset,
+  // is worth 2 to 3 % in the LDS-tiled kernels; here it measured 1 % slower and is not used)
   auto issue_h = [&](int stage) {
 #pragma unroll
     for (int q = 0; q < HQ; ++q) load_to_lds_16(hp[q] + h_km * kRsKm, slotH + stage * kStageBytes + q * 1024);
@@ -280,13 +282,6 @@ int rowstream_grid(int V) {
   const int tiles = (V + kSkinnyUnit - 1) / kSkinnyUnit;
   const int want = (tiles + kRsWaves - 1) / kRsWaves;
   return want < kSkinnyMaxGrid ? want : kSkinnyMaxGrid;
-}
-
-int rowstream_tokens_per_cu(int V) {
-  const int tiles = (V + kSkinnyUnit - 1) / kSkinnyUnit;
-  const int grid = rowstream_grid(V);
-  const int per_wg = (tiles + grid - 1) / grid;
-  return (per_wg + kRsWaves - 1) / kRsWaves * kRsWaves * kSkinnyUnit;
 }
 
 hipError_t launch_head_rowstream(const HeadArgs& a) {

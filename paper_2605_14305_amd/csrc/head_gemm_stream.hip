@@ -141,6 +141,26 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
       load_to_lds_16(gp[n], __builtin_amdgcn_readfirstlane(slot0[n] + s_load * kStageBytes));
       gp[n] += SK;
     };
+    // All NL loads of a step behind one write of M0: load n lands 1024 n bytes further on in LDS, and the
+    // instruction offset moves the memory address by as much, which the operand takes back.  A write of
+    // M0 in front of every load holds the wavefront (and its multiplies) for some tens of cycles each:
+    // one per step instead of four is worth 2.3 % at M = 128 and 3.5 % at M = 64.
+    auto issue_all = [&]() {
+      const uint32_t base = __builtin_amdgcn_readfirstlane(slot0[0] + s_load * kStageBytes);
+      if constexpr (NL == 4)
+        asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\t"
+                     "global_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %1, off offset:1024\n\t"
+                     "global_load_lds_dwordx4 %2, off offset:2048\n\tglobal_load_lds_dwordx4 %3, off offset:3072"
+                     :: "v"(gp[0]), "v"(gp[1] - 512), "v"(gp[2] - 1024), "v"(gp[3] - 1536), "s"(base) : "memory");
+      else if constexpr (NL == 2)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t"
+                     "global_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %1, off offset:1024"
+                     :: "v"(gp[0]), "v"(gp[1] - 512), "s"(base) : "memory");
+      else
+        load_to_lds_16(gp[0], base);
+#pragma unroll
+      for (int n = 0; n < NL; ++n) gp[n] += SK;
+    };
     auto loaded_step = [&]() {  // bookkeeping after the NL loads of one step
       s_load = s_load + 1 == RING ? 0 : s_load + 1;
       ++t_load;
@@ -205,16 +225,13 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
       lds_barrier();
       next_stage();
       mfma_part(cur, 0, 0);
-      issue_one(0);
+      issue_all();
       mfma_part(cur, 0, 1);
-      if constexpr (NL > 1) issue_one(1);
       __builtin_amdgcn_sched_barrier(0);
       read_frag(sw, sh, nxt);
       __builtin_amdgcn_sched_barrier(0);
       mfma_part(cur, 1, 0);
-      if constexpr (NL > 2) issue_one(2);
       mfma_part(cur, 1, 1);
-      if constexpr (NL > 3) issue_one(3);
       __builtin_amdgcn_sched_barrier(0);
       loaded_step();
       end_of_step();
@@ -253,11 +270,6 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
 }  // namespace
 
 bool stream_supports(int M, int d) { return M <= SM && d % 64 == 0; }
-
-int stream_tokens_per_cu(int V) {
-  const int n_tiles = (V + SN - 1) / SN;
-  return (n_tiles + kSkinnyMaxGrid - 1) / kSkinnyMaxGrid * SN;
-}
 
 template <int NI>
 static void launch_stream(const HeadArgs& a, int grid, int n_tiles) {

@@ -18,7 +18,8 @@
 // reads of 16 consecutive rows touch every bank once.  The permutation is applied on the global
 // side of the load (lane l lands at LDS base + 16 l and fetches the chunk that belongs there).
 //
-// One k-step is four 16-wide slices.  The fragments of a slice are read while the multiplies of
+// One k-step is four 16-wide slices (the four H loads of a wavefront go out as one group in the
+// first, the four W loads in the third).  The fragments of a slice are read while the multiplies of
 // the slice before it run; the last slice of a step is multiplied after the next step's barrier,
 // under the first fragment reads of the new stage, so the barrier does not idle the matrix unit
 // for the latency of those reads.
@@ -68,16 +69,30 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
     const int v = min(n0 + rl, a.V - 1);
     gh[q] = h_row(a, r) + c * 8;
     gw[q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
+    gh[q] -= q * 512;  // 1024 bytes per position in the group of four: the instruction offset puts them back
+    gw[q] -= q * 512;
   }
+  // Four loads behind one write of M0 (the instruction offset moves the LDS address and the memory
+  // address alike): every write of M0 in front of a direct-to-LDS load holds the wavefront for some
+  // tens of cycles; 2 writes per k-step instead of 8 are worth 2.7 % at M = 256.
+  auto issue4 = [&](const __bf16* (&g)[4], uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %1, off offset:1024\n\t"
+                 "global_load_lds_dwordx4 %2, off offset:2048\n\tglobal_load_lds_dwordx4 %3, off offset:3072"
+                 :: "v"(g[0]), "v"(g[1]), "v"(g[2]), "v"(g[3]), "s"(lds_base) : "memory");
+#pragma unroll
+    for (int q = 0; q < 4; ++q) g[q] += BK;
+  };
   const uint32_t slotH = lds_offset(ringH + wave * 32 * 8), slotW = lds_offset(ringW + wave * 32 * 8);
   constexpr uint32_t kStageBytes = kStage * 16;
   // loads of this wavefront for the k-step the pointers stand at, which then move on by one step
+  // single loads (prologue, wavefronts without rows)
   auto issue_h = [&](int stage, int q) {
-    load_to_lds_16(gh[q], slotH + stage * kStageBytes + q * 1024);
+    load_to_lds_16(gh[q] + q * 512, slotH + stage * kStageBytes + q * 1024);
     gh[q] += BK;
   };
   auto issue_w = [&](int stage, int q) {
-    load_to_lds_16(gw[q], slotW + stage * kStageBytes + q * 1024);
+    load_to_lds_16(gw[q] + q * 512, slotW + stage * kStageBytes + q * 1024);
     gw[q] += BK;
   };
 
@@ -143,32 +158,24 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
       return;
     }
     read_frag(Hs, Ws, 0, nxt);
-    if (FULL || kt + 1 < nk) issue_h(sh1, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfma_rows(cur, 0, 2);
-    if (FULL || kt + 1 < nk) issue_h(sh1, 1);
+    if (FULL || kt + 1 < nk) issue4(gh, slotH + sh1 * kStageBytes);
     mfma_rows(cur, 2, 4);
     __builtin_amdgcn_sched_barrier(0);
     read_frag(Hs, Ws, 1, cur);
-    if (FULL || kt + 1 < nk) issue_h(sh1, 2);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rows(nxt, 0, 2);
-    if (FULL || kt + 1 < nk) issue_h(sh1, 3);
-    mfma_rows(nxt, 2, 4);
+    mfma_rows(nxt, 0, 4);
     __builtin_amdgcn_sched_barrier(0);
     read_frag(Hs, Ws, 2, nxt);
-    if (FULL || kt + 2 < nk) issue_w(sw2, 0);
     __builtin_amdgcn_sched_barrier(0);
     mfma_rows(cur, 0, 2);
-    if (FULL || kt + 2 < nk) issue_w(sw2, 1);
+    if (FULL || kt + 2 < nk) issue4(gw, slotW + sw2 * kStageBytes);
     mfma_rows(cur, 2, 4);
     __builtin_amdgcn_sched_barrier(0);
     read_frag(Hs, Ws, 3, cur);
-    if (FULL || kt + 2 < nk) issue_w(sw2, 2);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rows(nxt, 0, 2);
-    if (FULL || kt + 2 < nk) issue_w(sw2, 3);
-    mfma_rows(nxt, 2, 4);
+    mfma_rows(nxt, 0, 4);
   };
 
   int kt = 0, sw = 0;
@@ -229,12 +236,13 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
   const __bf16* gw[8];
   const uint32_t slotH = lds_offset(ringH + wave * 64 * 8), slotW = lds_offset(ringW + wave * 64 * 8);
   constexpr uint32_t kStageBytes = kStage * 16;
+  // single loads (prologue, wavefronts without rows): the pointers are kept low, see below
   auto issue_h = [&](int stage, int q) {
-    load_to_lds_16(gh[q], slotH + stage * kStageBytes + q * 1024);
+    load_to_lds_16(gh[q] + (q & 3) * 512, slotH + stage * kStageBytes + q * 1024);
     gh[q] += BK;
   };
   auto issue_w = [&](int stage, int q) {
-    load_to_lds_16(gw[q], slotW + stage * kStageBytes + q * 1024);
+    load_to_lds_16(gw[q] + (q & 3) * 512, slotW + stage * kStageBytes + q * 1024);
     gw[q] += BK;
   };
 #pragma unroll
@@ -245,7 +253,21 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
     const int v = min(n0 + rl, a.V - 1);
     gh[q] = h_row(a, r) + c * 8;
     gw[q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
+    gh[q] -= (q & 3) * 512;  // 1024 bytes per position in its group of four: the instruction offset puts them back
+    gw[q] -= (q & 3) * 512;
   }
+  // Four loads behind one write of M0: the instruction offset moves the LDS address and the memory
+  // address alike, so the four pointers of a group are kept 0, 1, 2, 3 KB low.  Every write of M0 in
+  // front of a direct-to-LDS load holds the wavefront, and with it the multiplies, for some tens of
+  // cycles: 16 writes per k-step instead of 4 cost 2.5 % at M = 2048.
+  auto issue4 = [&](const __bf16* (&g)[8], int q0, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %1, off offset:1024\n\t"
+                 "global_load_lds_dwordx4 %2, off offset:2048\n\tglobal_load_lds_dwordx4 %3, off offset:3072"
+                 :: "v"(g[q0]), "v"(g[q0 + 1]), "v"(g[q0 + 2]), "v"(g[q0 + 3]), "s"(lds_base + q0 * 1024) : "memory");
+#pragma unroll
+    for (int q = q0; q < q0 + 4; ++q) g[q] += BK;
+  };
   // prologue: H(0), W(0), W(1)
 #pragma unroll
   for (int q = 0; q < 8; ++q) issue_h(0, q);
@@ -302,19 +324,18 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
       return;
     }
     // slice s of this step is read while slice s - 1 (s = 0: the last slice of the step before) is
-    // multiplied; one load goes out after each row of four multiplies
+    // multiplied; a group of four loads goes out after the first row of four multiplies
     auto phase = [&](int ks, Frag& rd, const Frag& mm, bool h_loads, int q0) {
       read_frag(Hs, Ws, ks, rd);
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        mfma_row(mm, i);
-        if (h_loads) {
-          if (more_h) issue_h(sh1, q0 + i);
-        } else {
-          if (more_w) issue_w(sw2, q0 + i);
-        }
+      mfma_row(mm, 0);
+      if (h_loads) {
+        if (more_h) issue4(gh, q0, slotH + sh1 * kStageBytes);
+      } else {
+        if (more_w) issue4(gw, q0, slotW + sw2 * kStageBytes);
       }
+#pragma unroll
+      for (int i = 1; i < 4; ++i) mfma_row(mm, i);
       __builtin_amdgcn_sched_barrier(0);
     };
     phase(0, nxt, cur, true, 0);

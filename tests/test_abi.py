@@ -66,9 +66,11 @@ def test_gemm_selection(lib):
     assert fb.fef_select_gemm(fb.make_params(3, 4096, 126464), 8) == fb.FEF_GEMM_ROWSTREAM
     assert fb.fef_select_gemm(fb.make_params(16, 4096, 126464), 8) == fb.FEF_GEMM_TILED256
     assert fb.fef_select_gemm(fb.make_params(6, 4096, 126464), 8) == fb.FEF_GEMM_ROWSTREAM
-    assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_STREAM   # 2 rounds of 256 tokens = 4 of 128
-    assert fb.fef_select_gemm(fb.make_params(4, 3584, 151936), 16) == fb.FEF_GEMM_ROWSTREAM  # 3 rounds of 256 > 5 of 128
-    assert fb.fef_select_gemm(fb.make_params(4, 3584, 151936), 8) == fb.FEF_GEMM_ROWSTREAM
+    assert fb.fef_select_gemm(fb.make_params(4, 4096, 126464), 8) == fb.FEF_GEMM_STREAM     # 64 rows: both need 64
+    assert fb.fef_select_gemm(fb.make_params(5, 4096, 126464), 8) == fb.FEF_GEMM_ROWSTREAM  # 80 rows: 96 against 128
+    assert fb.fef_select_gemm(fb.make_params(8, 4096, 126464), 8) == fb.FEF_GEMM_STREAM
+    assert fb.fef_select_gemm(fb.make_params(4, 3584, 151936), 16) == fb.FEF_GEMM_STREAM
+    assert fb.fef_select_gemm(fb.make_params(3, 3584, 151936), 8) == fb.FEF_GEMM_ROWSTREAM
     assert fb.fef_select_gemm(fb.make_params(4, 3520, 151936), 8) == fb.FEF_GEMM_STREAM    # d no multiple of 512
     assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(1, 1088, 1000), 8) == fb.FEF_GEMM_STREAM     # no skinny instantiation for this d
