@@ -259,7 +259,8 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
   // Four loads behind one write of M0: the instruction offset moves the LDS address and the memory
   // address alike, so the four pointers of a group are kept 0, 1, 2, 3 KB low.  Every write of M0 in
   // front of a direct-to-LDS load holds the wavefront, and with it the multiplies, for some tens of
-  // cycles: 16 writes per k-step instead of 4 cost 2.5 % at M = 2048.
+  // cycles: 16 writes per k-step instead of 4 cost 2.5 % at M = 2048.  (Groups of eight, with offsets
+  // -4096 ... 3072, measured 4 % slower than groups of four: eight loads in a row keep the multiplies waiting.)
   auto issue4 = [&](const __bf16* (&g)[8], int q0, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\t"
                  "global_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %1, off offset:1024\n\t"
