@@ -74,6 +74,13 @@ def test_gemm_selection(lib):
     assert fb.fef_select_gemm(fb.make_params(4, 3520, 151936), 8) == fb.FEF_GEMM_STREAM    # d no multiple of 512
     assert fb.fef_select_gemm(fb.make_params(1, 1024, 1000), 8) == fb.FEF_GEMM_SKINNY
     assert fb.fef_select_gemm(fb.make_params(1, 1088, 1000), 8) == fb.FEF_GEMM_STREAM     # no skinny instantiation for this d
+    # the whole table of AUTO at the LLaDA shape, by rows through the head (M = 2 B K)
+    for B in range(1, 160):
+        M = 2 * B
+        want = (fb.FEF_GEMM_SKINNY if M <= 32 else
+                fb.FEF_GEMM_ROWSTREAM if M <= 48 or 64 < M <= 96 else
+                fb.FEF_GEMM_STREAM if M <= 128 else fb.FEF_GEMM_TILED256)
+        assert fb.fef_select_gemm(fb.make_params(B, 4096, 126464), 1) == want, M
     p = fb.make_params(9, 4096, 126464, gemm_variant=fb.FEF_GEMM_STREAM)
     assert fb.fef_select_gemm(p, 8) == fb.FEF_ERR_UNSUPPORTED
     assert fb.fef_select_gemm(fb.make_params(1, 64, 32, dtype=fb.FEF_F32), 4) == fb.FEF_GEMM_F32
