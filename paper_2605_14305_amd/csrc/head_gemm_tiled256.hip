@@ -236,13 +236,12 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
   const __bf16* gw[8];
   const uint32_t slotH = lds_offset(ringH + wave * 64 * 8), slotW = lds_offset(ringW + wave * 64 * 8);
   constexpr uint32_t kStageBytes = kStage * 16;
-  // single loads (prologue, wavefronts without rows): the pointers are kept low, see below
   auto issue_h = [&](int stage, int q) {
-    load_to_lds_16(gh[q] + (q & 3) * 512, slotH + stage * kStageBytes + q * 1024);
+    load_to_lds_16(gh[q], slotH + stage * kStageBytes + q * 1024);
     gh[q] += BK;
   };
   auto issue_w = [&](int stage, int q) {
-    load_to_lds_16(gw[q] + (q & 3) * 512, slotW + stage * kStageBytes + q * 1024);
+    load_to_lds_16(gw[q], slotW + stage * kStageBytes + q * 1024);
     gw[q] += BK;
   };
 #pragma unroll
@@ -253,22 +252,7 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
     const int v = min(n0 + rl, a.V - 1);
     gh[q] = h_row(a, r) + c * 8;
     gw[q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
-    gh[q] -= (q & 3) * 512;  // 1024 bytes per position in its group of four: the instruction offset puts them back
-    gw[q] -= (q & 3) * 512;
   }
-  // Four loads behind one write of M0: the instruction offset moves the LDS address and the memory
-  // address alike, so the four pointers of a group are kept 0, 1, 2, 3 KB low.  Every write of M0 in
-  // front of a direct-to-LDS load holds the wavefront, and with it the multiplies, for some tens of
-  // cycles: 16 writes per k-step instead of 4 cost 2.5 % at M = 2048.  (Groups of eight, with offsets
-  // -4096 ... 3072, measured 4 % slower than groups of four: eight loads in a row keep the multiplies waiting.)
-  auto issue4 = [&](const __bf16* (&g)[8], int q0, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %4\n\ts_nop 0\n\t"
-                 "global_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %1, off offset:1024\n\t"
-                 "global_load_lds_dwordx4 %2, off offset:2048\n\tglobal_load_lds_dwordx4 %3, off offset:3072"
-                 :: "v"(g[q0]), "v"(g[q0 + 1]), "v"(g[q0 + 2]), "v"(g[q0 + 3]), "s"(lds_base + q0 * 1024) : "memory");
-#pragma unroll
-    for (int q = q0; q < q0 + 4; ++q) g[q] += BK;
-  };
   // prologue: H(0), W(0), W(1)
 #pragma unroll
   for (int q = 0; q < 8; ++q) issue_h(0, q);
@@ -281,11 +265,11 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
 
   floatx16 acc[2][4][2];  // [64-token half][32-row tile][32-token tile]
   struct Frag { bf16x8 a[4], b[4]; };
-  auto read_frag = [&](const bf16x8* Hs, const bf16x8* Ws, int ks, Frag& f) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) f.a[i] = Hs[swz(wm * 128 + i * 32 + j32, ks * 2 + h)];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) f.b[j] = Ws[swz(wn * 128 + j * 32 + j32, ks * 2 + h)];
+  // fragment n of slice ks in the order the next slice's multiplies want them: a0, b0, b1, b2, b3, a1, a2, a3
+  auto read_one = [&](const bf16x8* Hs, const bf16x8* Ws, int ks, Frag& f, int n) {
+    if (n == 0) f.a[0] = Hs[swz(wm * 128 + j32, ks * 2 + h)];
+    else if (n <= 4) f.b[n - 1] = Ws[swz(wn * 128 + (n - 1) * 32 + j32, ks * 2 + h)];
+    else f.a[n - 4] = Hs[swz(wm * 128 + (n - 4) * 32 + j32, ks * 2 + h)];
   };
   auto mfma_row = [&](const Frag& f, int i) {
 #pragma unroll
@@ -324,20 +308,34 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
         for (int q = 0; q < 8; ++q) issue_w(sw2, q);
       return;
     }
-    // slice s of this step is read while slice s - 1 (s = 0: the last slice of the step before) is
-    // multiplied; a group of four loads goes out after the first row of four multiplies
+    // Slice s of this step is read while slice s - 1 (s = 0: the last slice of the step before) is
+    // multiplied.  With one wavefront per SIMD the matrix unit has nothing to run while this wavefront
+    // issues anything else, and it holds only one multiply beyond the one in work: a run of eight
+    // fragment reads or four loads between two multiplies leaves it idle for the length of the run
+    // (in a loop of multiplies, reads, loads and barriers only: 1837 TFLOP/s with the reads and loads
+    // of a slice in runs, 2270 with one read after every second multiply and one load after the first
+    // multiply of each row; multiplies alone 2460).  So everything is dealt out singly.
     auto phase = [&](int ks, Frag& rd, const Frag& mm, bool h_loads, int q0) {
-      read_frag(Hs, Ws, ks, rd);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_row(mm, 0);
-      if (h_loads) {
-        if (more_h) issue4(gh, q0, slotH + sh1 * kStageBytes);
-      } else {
-        if (more_w) issue4(gw, q0, slotW + sw2 * kStageBytes);
-      }
 #pragma unroll
-      for (int i = 1; i < 4; ++i) mfma_row(mm, i);
-      __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          acc[j >> 1][i][j & 1] =
+              __builtin_amdgcn_mfma_f32_32x32x16_bf16(mm.a[i], mm.b[j], acc[j >> 1][i][j & 1], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (j & 1) {
+            read_one(Hs, Ws, ks, rd, i * 2 + (j >> 1));
+            __builtin_amdgcn_sched_barrier(0);
+          } else if (j == 0) {
+            if (h_loads) {
+              if (more_h) issue_h(sh1, q0 + i);
+            } else {
+              if (more_w) issue_w(sw2, q0 + i);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
     };
     phase(0, nxt, cur, true, 0);
     phase(1, cur, nxt, true, 4);
