@@ -236,13 +236,18 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
   const __bf16* gw[8];
   const uint32_t slotH = lds_offset(ringH + wave * 64 * 8), slotW = lds_offset(ringW + wave * 64 * 8);
   constexpr uint32_t kStageBytes = kStage * 16;
+  // The pointer moves on right behind its load (the empty statement pins the addition there): left to
+  // itself the compiler gathers the sixteen 64-bit additions of a step in front of the barrier, a run
+  // during which the matrix unit has nothing to do.
   auto issue_h = [&](int stage, int q) {
     load_to_lds_16(gh[q], slotH + stage * kStageBytes + q * 1024);
     gh[q] += BK;
+    asm volatile("" : "+v"(gh[q]));
   };
   auto issue_w = [&](int stage, int q) {
     load_to_lds_16(gw[q], slotW + stage * kStageBytes + q * 1024);
     gw[q] += BK;
+    asm volatile("" : "+v"(gw[q]));
   };
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
@@ -277,7 +282,8 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
       acc[j >> 1][i][j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[j >> 1][i][j & 1], 0, 0, 0);
   };
 
-  const bool idle = m0 + wm * 128 >= M;  // none of this wavefront's rows exists: loads and barriers only
+  // none of this wavefront's rows exists: loads and barriers only (wavefront-uniform, and said so)
+  const bool idle = __builtin_amdgcn_readfirstlane((int)(m0 + wm * 128 >= M)) != 0;
 #pragma unroll
   for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -289,8 +295,9 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
   for (int i = 0; i < 4; ++i) cur.a[i] = cur.b[i] = bf16x8{};  // "last slice of step -1": multiplies by zero
 
   // One k-step; outstanding loads of this wavefront on entry, oldest first: H(kt) [8], W(kt+1) [8].
-  auto step = [&](int kt, int sh, int sw, auto full) {
+  auto step = [&](int kt, int sh, int sw, auto full, auto idle_tag) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full)::value;
+    constexpr bool IDLE = decltype(idle_tag)::value;
     const bf16x8* Hs = ringH + sh * kStage;
     const bf16x8* Ws = ringW + sw * kStage;
     const int sh1 = sh ^ 1, sw2 = sw == 0 ? 2 : sw - 1;
@@ -299,7 +306,7 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
     if (more_h) wait_newer<8>();
     else wait_newer<0>();
     lds_barrier();
-    if (idle) {
+    if constexpr (IDLE) {
       if (more_h)
 #pragma unroll
         for (int q = 0; q < 8; ++q) issue_h(sh1, q);
@@ -343,18 +350,27 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
     phase(3, cur, nxt, false, 4);
   };
 
-  int kt = 0, sw = 0;
-  for (; kt + 3 < nk; kt += 2) {  // two full steps: kt + 1 + 2 < nk
-    step(kt, 0, sw, std::true_type{});
-    sw = sw == 2 ? 0 : sw + 1;
-    step(kt + 1, 1, sw, std::true_type{});
-    sw = sw == 2 ? 0 : sw + 1;
+  // Two copies of the loop, chosen once: a wavefront without rows only loads and meets the barriers.  (With
+  // the choice inside the step the two paths meet again in every step, and the compiler reconciles their
+  // registers there with sixteen moves in front of the barrier.)
+  auto walk = [&](auto idle_tag) __attribute__((always_inline)) {
+    int kt = 0, sw = 0;
+    for (; kt + 3 < nk; kt += 2) {  // two full steps: kt + 1 + 2 < nk
+      step(kt, 0, sw, std::true_type{}, idle_tag);
+      sw = sw == 2 ? 0 : sw + 1;
+      step(kt + 1, 1, sw, std::true_type{}, idle_tag);
+      sw = sw == 2 ? 0 : sw + 1;
+    }
+    for (; kt < nk; ++kt) {
+      step(kt, kt & 1, sw, std::false_type{}, idle_tag);
+      sw = sw == 2 ? 0 : sw + 1;
+    }
+  };
+  if (idle) {
+    walk(std::true_type{});
+    return;
   }
-  for (; kt < nk; ++kt) {
-    step(kt, kt & 1, sw, std::false_type{});
-    sw = sw == 2 ? 0 : sw + 1;
-  }
-  if (idle) return;
+  walk(std::false_type{});
 #pragma unroll
   for (int i = 0; i < 4; ++i) mfma_row(cur, i);  // last slice of the last step
 
