@@ -93,6 +93,14 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
       for (int j = 0; j < 2; ++j) f.b[ks][j] = Bs[fb[ks][j]];
     }
   };
+  // fragment r of a stage, in the order the multiplies use them: slice 0 (a.., b0, b1), then slice 1
+  auto read_one = [&](int sw, int sh, Frag<NI>& f, int r) {
+    const bf16x8* As = ringH + sh * kStageH;
+    const bf16x8* Bs = ringW + sw * kStageW;
+    const int ks = r / (NI + 2), q = r % (NI + 2);
+    if (q < NI) f.a[ks][q] = As[fa[ks][q]];
+    else f.b[ks][q - NI] = Bs[fb[ks][q - NI]];
+  };
   // The multiplies of one k-slice in two parts: row tile `part` when NI = 2, token tile `part` when NI = 1.
   auto mfma_part = [&](const Frag<NI>& f, int ks, int part) {
     if constexpr (NI == 1) {
@@ -224,15 +232,33 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
       wait_newer<(LEAD - 2) * NL>();
       lds_barrier();
       next_stage();
-      mfma_part(cur, 0, 0);
-      issue_all();
-      mfma_part(cur, 0, 1);
-      __builtin_amdgcn_sched_barrier(0);
-      read_frag(sw, sh, nxt);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_part(cur, 1, 0);
-      mfma_part(cur, 1, 1);
-      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (NI == 2) {
+        // 128-row tiles: the eight multiplies of the step in order, one fragment read of the next stage after each
+        // (in the order the next step uses them), the loads after the second: -2 % against reading the eight
+        // fragments in one run.  (With 64-row tiles, four multiplies and six reads per step, the run is faster.)
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+          const int ks = n >> 2, i = (n >> 1) & 1, j = n & 1;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[ks][i], cur.b[ks][j], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          read_one(sw, sh, nxt, n);
+          __builtin_amdgcn_sched_barrier(0);
+          if (n == 1) {
+            issue_all();
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      } else {
+        mfma_part(cur, 0, 0);
+        issue_all();
+        mfma_part(cur, 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frag(sw, sh, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_part(cur, 1, 0);
+        mfma_part(cur, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
       loaded_step();
       end_of_step();
     };
