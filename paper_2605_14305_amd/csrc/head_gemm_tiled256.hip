@@ -56,6 +56,13 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
   const int nt = xcd + 8 * (seq / m_tiles), mt = seq % m_tiles;
   if (nt >= n_tiles) return;
   const int m0 = mt * BM, n0 = nt * BN;
+  const int nk = a.d / BK;
+  // Every row of W starts at a multiple of 2 d bytes, so workgroups that walk k from 0 in step ask HBM for the
+  // same low address bits at the same moment: each token tile starts its walk at another k-step and wraps
+  // (M = 256: head 277 -> 263 us, step 326 -> 321.5 us; with several row tiles per token tile, which share H
+  // in time through L2, the same change measured +2 % at M = 2048 and is not used there).
+  const int k0 = (int)((unsigned)(nt * 37) % (unsigned)nk);
+  int h_left = nk - k0, w_left = nk - k0;  // steps until the walk is back at k = 0
 
   // Direct-to-LDS loads: wavefront w fills rows [32 w, 32 w + 32) of an H stage and of a W stage,
   // 8 rows per instruction; lane l owns LDS slot (row 8 q + l / 8, position l % 8).
@@ -67,8 +74,8 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
     const int c = (lane & 7) ^ ((rl >> 1) & 7);
     const int r = min(m0 + rl, M - 1);      // rows past M / V re-read the last row; masked in the epilogue
     const int v = min(n0 + rl, a.V - 1);
-    gh[q] = h_row(a, r) + c * 8;
-    gw[q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8;
+    gh[q] = h_row(a, r) + c * 8 + k0 * BK;
+    gw[q] = (const __bf16*)a.W + (size_t)v * a.d + c * 8 + k0 * BK;
     gh[q] -= q * 512;  // 1024 bytes per position in the group of four: the instruction offset puts them back
     gw[q] -= q * 512;
   }
@@ -96,6 +103,17 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
     gw[q] += BK;
   };
 
+  auto wrap_h = [&]() {  // after the H loads of a step
+    if (--h_left == 0)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) gh[q] -= a.d;
+  };
+  auto wrap_w = [&]() {
+    if (--w_left == 0)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) gw[q] -= a.d;
+  };
+
   floatx16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -111,17 +129,19 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
   };
 
-  const int nk = a.d / BK;
   const bool idle = m0 + wm * 128 >= M;  // none of this wavefront's rows exists: loads and barriers only
 
   // prologue: H(0), W(0), W(1)
 #pragma unroll
   for (int q = 0; q < 4; ++q) issue_h(0, q);
+  wrap_h();
 #pragma unroll
   for (int q = 0; q < 4; ++q) issue_w(0, q);
+  wrap_w();
   if (1 < nk) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) issue_w(1, q);
+    wrap_w();
   }
 
   Frag cur, nxt;
@@ -143,12 +163,16 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
     else wait_newer<0>();
     lds_barrier();
     if (idle) {
-      if (FULL || kt + 1 < nk)
+      if (FULL || kt + 1 < nk) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) issue_h(sh1, q);
-      if (FULL || kt + 2 < nk)
+        wrap_h();
+      }
+      if (FULL || kt + 2 < nk) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) issue_w(sw2, q);
+        wrap_w();
+      }
       return;
     }
     // Reads dealt out one after each multiply, in the order the next slice wants them, and the group of four
@@ -170,8 +194,14 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
           __builtin_amdgcn_sched_barrier(0);
         }
         if (n == 6) {
-          if (loads == 1 && (FULL || kt + 1 < nk)) issue4(gh, slotH + sh1 * kStageBytes);
-          if (loads == 2 && (FULL || kt + 2 < nk)) issue4(gw, slotW + sw2 * kStageBytes);
+          if (loads == 1 && (FULL || kt + 1 < nk)) {
+            issue4(gh, slotH + sh1 * kStageBytes);
+            wrap_h();
+          }
+          if (loads == 2 && (FULL || kt + 2 < nk)) {
+            issue4(gw, slotW + sw2 * kStageBytes);
+            wrap_w();
+          }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
