@@ -112,9 +112,15 @@ __device__ inline float max_ror(float x) {
 //
 // CE = true is the cross-entropy use of the head: nothing is written but the partials and, for
 // the lane that holds a row's label token, that token's scaled logit.
+//
+// lds_part != nullptr: the partials do not go to memory but to LDS, [row of the workgroup tile][4 token
+// groups of 64], for the caller to merge into one partial per (row, workgroup tile); mw_local is the
+// wavefront's first row inside the workgroup tile and lcol its token group.  A wavefront whose tokens all
+// lie past V then leaves (-inf, 0).
 template <int NI, bool CE = false, int RB = 16>
 __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, floatx16 (&acc)[NI][2], int mw, int vbase,
-                                                 int M, int lane) {
+                                                 int M, int lane, float2* lds_part = nullptr, int mw_local = 0,
+                                                 int lcol = 0) {
   static_assert(RB == 4 || RB == 8 || RB == 16, "accumulator indices per batch");
   constexpr float kLog2e = 1.4426950408889634f;
   const int j32 = lane & 31, h = lane >> 5;
@@ -122,7 +128,16 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
   const int ptile = vbase / kTiledTn;
   const int v0 = vbase + j32, v1 = v0 + 32;
   float* lbase = CE ? nullptr : a.logits + (size_t)(mw + 4 * h) * a.ldl + v0;
-  float2* pbase = a.partials + (size_t)(mw + 4 * h) * a.nT + ptile;
+  float2* pbase = lds_part ? lds_part + (mw_local + 4 * h) * 4 + lcol : a.partials + (size_t)(mw + 4 * h) * a.nT + ptile;
+  const size_t pstride = lds_part ? 4 : (size_t)a.nT;
+  if (lds_part && vbase >= a.V) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (j32 == 0) pbase[(i * 32 + 8 * (r >> 2) + (r & 3)) * pstride] = make_float2(-INFINITY, 0.f);
+    return;
+  }
   if (mw + 32 * NI <= M && vbase + 64 <= a.V) {  // interior: wavefront-uniform
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
@@ -188,7 +203,7 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
         for (int q = 0; q < RB; ++q) {
           const int r = rb + q;
           const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
-          pbase[(size_t)mr * a.nT] = make_float2(mx[q], e[q] + t[q]);
+          pbase[(size_t)mr * pstride] = make_float2(mx[q], e[q] + t[q]);
         }
       }
     }
@@ -217,7 +232,7 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
         float e = (ok0 ? exp2f(fmaf(l0, kLog2e, -mb)) : 0.f) + (ok1 ? exp2f(fmaf(l1, kLog2e, -mb)) : 0.f);
         e = row16_sum(e);
         e += swap16(e);
-        if (j32 == 0 && row_ok) pbase[(size_t)mr * a.nT] = make_float2(mx, e);
+        if (j32 == 0 && (row_ok || lds_part)) pbase[(size_t)mr * pstride] = make_float2(row_ok ? mx : -INFINITY, row_ok ? e : 0.f);
       }
     }
   }

@@ -42,6 +42,23 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kStage = BM * 8;   // 16-byte chunks per operand stage (BM == BN)
 constexpr int kRingH = 2, kRingW = 3;
 
+// One (max, sum exp) partial per (row, workgroup tile of 256 tokens): the four 64-token partials the epilogue
+// left in LDS, merged in a fixed order by the thread that owns the row.  A quarter of the partials for the
+// kernels that read them next.
+__device__ inline void merge_tile_partials(const HeadArgs& a, const float2* lp, int m0, int nt, int M, int tid) {
+  constexpr float kLog2e = 1.4426950408889634f;
+  if (tid < BM && m0 + tid < M) {
+    float2 p[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) p[c] = lp[tid * 4 + c];
+    const float mx = fmaxf(fmaxf(p[0].x, p[1].x), fmaxf(p[2].x, p[3].x));  // finite: the tile's first token exists
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sum += p[c].y * exp2f((p[c].x - mx) * kLog2e);
+    a.partials[(size_t)(m0 + tid) * a.nT + nt] = make_float2(mx, sum);
+  }
+}
+
 template <bool CE>
 __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_tiles, int n_tiles) {
   __shared__ bf16x8 ringH[kRingH * kStage];  // 64 KB
@@ -223,10 +240,13 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
     step(kt, kt & 1, sw, std::false_type{});
     sw = sw == 2 ? 0 : sw + 1;
   }
-  if (idle) return;
-  mfma_rows(cur, 0, 4);  // last slice of the last step
+  if (!idle) mfma_rows(cur, 0, 4);  // last slice of the last step
 
-  store_logits_and_partials<4, CE>(a, acc, m0 + wm * 128, n0 + wn * 64, M, lane);
+  lds_barrier();  // nobody reads the rings any more: the H ring takes the partials
+  float2* lp = reinterpret_cast<float2*>(ringH);
+  if (!idle) store_logits_and_partials<4, CE>(a, acc, m0 + wm * 128, n0 + wn * 64, M, lane, lp, wm * 128, wn);
+  lds_barrier();
+  merge_tile_partials(a, lp, m0, nt, M, tid);
 }
 
 
@@ -400,16 +420,20 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
       sw = sw == 2 ? 0 : sw + 1;
     }
   };
+  float2* lp = reinterpret_cast<float2*>(ringH);
   if (idle) {
     walk(std::true_type{});
-    return;
-  }
-  walk(std::false_type{});
+    lds_barrier();
+  } else {
+    walk(std::false_type{});
 #pragma unroll
-  for (int i = 0; i < 4; ++i) mfma_row(cur, i);  // last slice of the last step
-
-  store_logits_and_partials<4, CE>(a, acc[0], m0 + wm * 128, n0 + wn * 128, M, lane);
-  store_logits_and_partials<4, CE>(a, acc[1], m0 + wm * 128, n0 + wn * 128 + 64, M, lane);
+    for (int i = 0; i < 4; ++i) mfma_row(cur, i);  // last slice of the last step
+    lds_barrier();  // nobody reads the rings any more: the H ring takes the partials
+    store_logits_and_partials<4, CE>(a, acc[0], m0 + wm * 128, n0 + wn * 128, M, lane, lp, wm * 128, 2 * wn);
+    store_logits_and_partials<4, CE>(a, acc[1], m0 + wm * 128, n0 + wn * 128 + 64, M, lane, lp, wm * 128, 2 * wn + 1);
+  }
+  lds_barrier();
+  merge_tile_partials(a, lp, m0, nt, M, tid);
 }
 
 }  // namespace

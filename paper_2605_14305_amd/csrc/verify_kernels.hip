@@ -770,6 +770,7 @@ __global__ void copy_logits_kernel(const float* __restrict__ src, long ldl, floa
 hipError_t launch_verify(const VerifyArgs& a) {
   const dim3 g1((a.nrows + NW - 1) / NW);
   if (a.nT <= 64 * 4) hipLaunchKernelGGL(row_lse_draft_kernel<4>, g1, dim3(NT), 0, a.stream, a);
+  else if (a.nT <= 64 * 8) hipLaunchKernelGGL(row_lse_draft_kernel<8>, g1, dim3(NT), 0, a.stream, a);
   else if (a.nT <= 64 * 40) hipLaunchKernelGGL(row_lse_draft_kernel<40>, g1, dim3(NT), 0, a.stream, a);
   else hipLaunchKernelGGL(row_lse_draft_kernel<0>, g1, dim3(NT), 0, a.stream, a);
   if (a.phase == 3) {
