@@ -82,7 +82,8 @@ typedef enum {
                           once, split-k; other d at M <= 32 go to STREAM (fef_select_gemm tells) */
   FEF_GEMM_TILED = 2,  /* bf16, any M: plain 128x128 LDS-tiled MFMA GEMM (never picked by AUTO) */
   FEF_GEMM_F32 = 3,    /* f32, any shape: reference-grade FMA kernel                       */
-  FEF_GEMM_TILED256 = 4, /* bf16, any M: 256x256 LDS-tiled MFMA GEMM (AUTO: M > 128)       */
+  FEF_GEMM_TILED256 = 4, /* bf16, any M: 256x256 LDS-tiled MFMA GEMM, eight wavefronts of 128x64 up to
+                            256 rows, four of 128x128 above (AUTO: M > 128)                  */
   FEF_GEMM_STREAM = 5,   /* bf16, M <= 128: all rows x 256 tokens per persistent workgroup, W
                             streamed through a deep LDS ring, 64- or 128-row tiles (AUTO: 32 < M <= 128
                             where the other streaming kernel is not chosen)                  */
