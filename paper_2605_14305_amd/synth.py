@@ -63,6 +63,8 @@ WORKLOADS = {
                           dtype="bf16", rho=0.9, logit_std=3.0),
     "llada_b32": Workload("llada_b32", B=32, K=8, block=32, gen_len=256, d=4096, V=126464,
                           dtype="bf16", rho=0.9, logit_std=3.0),
+    "dream_b1": Workload("dream_b1", B=1, K=16, block=64, gen_len=512, d=3584, V=151936,
+                         dtype="bf16", rho=0.95, logit_std=4.0),
     "dream_b4": Workload("dream_b4", B=4, K=16, block=64, gen_len=512, d=3584, V=151936,
                          dtype="bf16", rho=0.95, logit_std=4.0),
     "dream_b32": Workload("dream_b32", B=32, K=16, block=64, gen_len=512, d=3584, V=151936,
