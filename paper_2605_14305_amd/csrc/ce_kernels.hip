@@ -27,14 +27,28 @@ __global__ __launch_bounds__(NT) void ce_row_kernel(CeArgs a) {
   float ce = 0.f;
   if (lab >= 0) {  // wavefront-uniform
     const float2* P = a.partials + (size_t)r * a.nT;
-    float mx = -INFINITY;
-    for (int t = lane; t < a.nT; t += kWave) mx = fmaxf(mx, P[t].x);
-    mx = wave_max(mx);
-    float sm = 0.f;
-    for (int t = lane; t < a.nT; t += kWave) {
-      const float2 p = P[t];
-      sm += p.y * expf(p.x - mx);
+    // One pass: each lane merges its partials eight at a time (eight independent loads in
+    // flight), carrying a running (max, sum exp); the lanes' pairs are merged after the loop.
+    float mx = -INFINITY, sm = 0.f;
+    for (int t0 = lane; t0 < a.nT; t0 += 8 * kWave) {
+      float2 p[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int t = t0 + j * kWave;
+        p[j] = t < a.nT ? P[t] : make_float2(-INFINITY, 0.f);
+      }
+      float m8 = mx;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m8 = fmaxf(m8, p[j].x);
+      float s8 = sm > 0.f ? sm * expf(mx - m8) : 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s8 += p[j].y > 0.f ? p[j].y * expf(p[j].x - m8) : 0.f;
+      mx = m8;
+      sm = s8;
     }
+    const float wmx = wave_max(mx);
+    sm = sm > 0.f ? sm * expf(mx - wmx) : 0.f;
+    mx = wmx;
     sm = wave_sum(sm);
     ce = mx + logf(sm) - a.label_logit[r];
   }

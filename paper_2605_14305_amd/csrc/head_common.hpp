@@ -138,6 +138,29 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
         if (j32 == 0) pbase[(i * 32 + 8 * (r >> 2) + (r & 3)) * pstride] = make_float2(-INFINITY, 0.f);
     return;
   }
+  if constexpr (CE) {
+    // The label token's logit of a row lies in exactly one lane of one wavefront.  Most calls
+    // hold none (64 of V tokens, 32 NI rows): every lane looks up one or two of the rows' labels,
+    // and only a wavefront that finds one inside its 64 tokens goes through its elements.
+    bool hit = false;
+#pragma unroll
+    for (int r0 = 0; r0 < 32 * NI; r0 += kWave) {
+      const int row = mw + r0 + lane;
+      if (r0 + lane < 32 * NI && row < M) hit |= (unsigned)(a.labels[row] - vbase) < 64u;
+    }
+    if (__builtin_amdgcn_ballot_w64(hit) != 0 && vbase < a.V) {  // wavefront-uniform
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = mw + 4 * h + i * 32 + 8 * (r >> 2) + (r & 3);
+          const int lab = row < M ? a.labels[row] : -1;
+          if (v0 < a.V && lab == v0) a.label_logit[row] = acc[i][0][r] * sc;
+          if (v1 < a.V && lab == v1) a.label_logit[row] = acc[i][1][r] * sc;
+        }
+      }
+    }
+  }
   if (mw + 32 * NI <= M && vbase + 64 <= a.V) {  // interior: wavefront-uniform
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
@@ -154,12 +177,7 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
           const float l0 = acc[i][0][r] * sc, l1 = acc[i][1][r] * sc;
           acc[i][0][r] = l0;
           acc[i][1][r] = l1;
-          if constexpr (CE) {
-            const int row = mw + 4 * h + mr;
-            const int lab = a.labels[row];
-            if (lab == v0) a.label_logit[row] = l0;
-            if (lab == v1) a.label_logit[row] = l1;
-          } else {
+          if constexpr (!CE) {
             float* dst = lbase + (size_t)mr * a.ldl;
             // non-temporal: the logits are read next by another kernel, and as ordinary stores they
             // sit dirty in L2 and push out the W and H lines the neighbouring workgroups are about
@@ -216,12 +234,7 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
         const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
         const bool row_ok = mw + 4 * h + mr < M;
         const float l0 = acc[i][0][r] * sc, l1 = acc[i][1][r] * sc;
-        if constexpr (CE) {
-          const int row = mw + 4 * h + mr;
-          const int lab = row_ok ? a.labels[row] : -1;
-          if (ok0 && lab == v0) a.label_logit[row] = l0;
-          if (ok1 && lab == v1) a.label_logit[row] = l1;
-        } else {
+        if constexpr (!CE) {
           float* dst = lbase + (size_t)mr * a.ldl;
           if (row_ok && ok0) dst[0] = l0;
           if (row_ok && ok1) dst[32] = l1;

@@ -636,11 +636,15 @@ def test_separate_draft_model_head(B, K, d, V):
 
 
 @pytest.mark.parametrize("B,K,d,V,variant", [(1, 8, 512, 3000, fb.FEF_GEMM_AUTO), (2, 8, 512, 3000, fb.FEF_GEMM_AUTO),
-                                              (6, 4, 128, 1000, fb.FEF_GEMM_TILED), (40, 4, 64, 700, fb.FEF_GEMM_TILED256)])
+                                              (6, 4, 128, 1000, fb.FEF_GEMM_TILED), (40, 4, 64, 700, fb.FEF_GEMM_TILED256),
+                                              (24, 4, 64, 700, fb.FEF_GEMM_TILED256)])
 def test_split_draft_then_target_call_order(B, K, d, V, variant):
     """The method's own call order: draft laws and draft tokens first, target laws afterwards
     (the verification inputs carry the draft prefix).  The two calls share the workspace; the
-    result equals the oracle's and, with the same head kernel, the fused call bit for bit."""
+    result equals the oracle's and, with the same head kernel, the fused call bit for bit.
+    (Above 256 rows the 256 x 256 variant runs its four-wavefront kernel, whose interior tiles sum
+    exp over 128 tokens at once and its edge tiles over 64 and 64: a row's partials then depend on
+    where its tile lies, and the fused call is held to the oracle instead.)"""
     block = 16
     W = synth.make_head(V, d, 8)
     hd, ht = synth.make_hidden(B, K, d, 8, 0.8, 3.0 / (0.02 * np.sqrt(d)))
@@ -671,8 +675,12 @@ def test_split_draft_then_target_call_order(B, K, d, V, variant):
         tok2, acc2, rem2 = vf(hdd, htd, Wd, 8, step=3, mask_in=md)
         torch.cuda.synchronize()
         fused = (_np(tok2), _np(acc2), _np(rem2), _np(vf.diag["logits"]), _np(vf.diag["alpha"]))
-        for x, y in zip(split, fused):
-            assert np.array_equal(x, y)
+        if used == fb.FEF_GEMM_TILED256 and 2 * B * K > 256:
+            st2 = parity.compare(ref, fused[0], fused[1], fused[2], {k: _np(v) for k, v in vf.diag.items()})
+            assert st2["near_flipped"] <= B // 20
+        else:
+            for x, y in zip(split, fused):
+                assert np.array_equal(x, y)
 
 
 @pytest.mark.parametrize("case", range(24))
