@@ -89,16 +89,52 @@ __device__ inline void wait_newer() {
 __device__ inline uint32_t lds_offset(const void* p) {
   return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)p);
 }
-// max(x, x rotated right by N inside its row of 16 lanes) in one instruction.  The s_nop covers
-// the two wait states a DPP read needs after a vector write of its source.
+// x_k = max(x_k, x_k rotated right by N lanes inside its row of 16), for G registers that do not depend on one
+// another, in one statement: the two wait states a DPP read needs after a vector write of its source are paid once
+// in front, not once per instruction.
 template <int N>
-__device__ inline float max_ror(float x) {
-  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "add the rotation");
+__device__ inline void max_ror_x8(float* x) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "rotation inside a row of 16 lanes");
+  asm("s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %1, %1, %1 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %2, %2, %2 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %3, %3, %3 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %4, %4, %4 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %5, %5, %5 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %6, %6, %6 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %7, %7, %7 row_ror:%8 row_mask:0xf bank_mask:0xf"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+      : "n"(N));
+}
+template <int N>
+__device__ inline void max_ror_x4(float* x) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "rotation inside a row of 16 lanes");
+  asm("s_nop 1\n\t"
+      "v_max_f32_dpp %0, %0, %0 row_ror:%4 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %1, %1, %1 row_ror:%4 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %2, %2, %2 row_ror:%4 row_mask:0xf bank_mask:0xf\n\t"
+      "v_max_f32_dpp %3, %3, %3 row_ror:%4 row_mask:0xf bank_mask:0xf"
+      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])
+      : "n"(N));
+}
+// RB registers, RB a multiple of 4
+template <int N, int RB>
+__device__ inline void max_ror_all(float* x) {
+  static_assert(RB % 4 == 0, "groups of eight and four");
+#pragma unroll
+  for (int q = 0; q + 8 <= RB; q += 8) max_ror_x8<N>(x + q);
+  if constexpr (RB % 8 == 4) max_ror_x4<N>(x + RB - 4);
+}
+// max of numbers that are not NaN in one instruction (fmaxf also quiets signalling NaNs, which costs a second one)
+__device__ inline float vmax(float x, float y) {
   float r;
-  if constexpr (N == 8) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
-  if constexpr (N == 4) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:4 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
-  if constexpr (N == 2) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:2 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
-  if constexpr (N == 1) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:1 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+  return r;
+}
+__device__ inline float vmax3(float x, float y, float z) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
   return r;
 }
 
@@ -185,20 +221,16 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
             __builtin_nontemporal_store(l0, dst);
             __builtin_nontemporal_store(l1, dst + 32);
           }
-          mx[q] = l0 > l1 ? l0 : l1;
+          mx[q] = vmax(l0, l1);
         }
-#pragma unroll
-        for (int q = 0; q < RB; ++q) mx[q] = max_ror<8>(mx[q]);
-#pragma unroll
-        for (int q = 0; q < RB; ++q) mx[q] = max_ror<4>(mx[q]);
-#pragma unroll
-        for (int q = 0; q < RB; ++q) mx[q] = max_ror<2>(mx[q]);
-#pragma unroll
-        for (int q = 0; q < RB; ++q) mx[q] = max_ror<1>(mx[q]);
+        max_ror_all<8, RB>(mx);
+        max_ror_all<4, RB>(mx);
+        max_ror_all<2, RB>(mx);
+        max_ror_all<1, RB>(mx);
 #pragma unroll
         for (int q = 0; q < RB; ++q) e[q] = swap16(mx[q]);
 #pragma unroll
-        for (int q = 0; q < RB; ++q) mx[q] = mx[q] > e[q] ? mx[q] : e[q];
+        for (int q = 0; q < RB; ++q) mx[q] = vmax(mx[q], e[q]);
 #pragma unroll
         for (int q = 0; q < RB; ++q) {
           const float mb = mx[q] * kLog2e;

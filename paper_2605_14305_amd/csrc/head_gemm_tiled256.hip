@@ -42,22 +42,15 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kStage = BM * 8;   // 16-byte chunks per operand stage (BM == BN)
 constexpr int kRingH = 2, kRingW = 3;
 
-// One (max, sum exp) partial per (row, workgroup tile of 256 tokens): the four 64-token partials the epilogue
-// left in LDS, merged in a fixed order by the thread that owns the row.  A quarter of the partials for the
-// kernels that read them next.
-// wide != nullptr (four wavefronts of 128 x 128): wide[w] != 0 says that wavefront w (rows 128 (w / 2) ..,
-// tokens 128 (w % 2) ..) left ONE partial over its 128 tokens in the first slot of its pair and nothing in the second.
-__device__ inline void merge_tile_partials(const HeadArgs& a, const float2* lp, int m0, int nt, int M, int tid,
-                                           const int* wide = nullptr) {
+// One (max, sum exp) partial per (row, workgroup tile of 256 tokens): the four partials of a row that the epilogue
+// left in LDS (each over a quarter of the tile's tokens; which quarter is the epilogue's business), merged in a
+// fixed order by the thread that owns the row.  A quarter of the partials for the kernels that read them next.
+__device__ inline void merge_tile_partials(const HeadArgs& a, const float2* lp, int m0, int nt, int M, int tid) {
   constexpr float kLog2e = 1.4426950408889634f;
   if (tid < BM && m0 + tid < M) {
     float2 p[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) p[c] = lp[tid * 4 + c];
-    if (wide) {
-      if (wide[(tid >> 7) * 2]) p[1] = make_float2(-INFINITY, 0.f);
-      if (wide[(tid >> 7) * 2 + 1]) p[3] = make_float2(-INFINITY, 0.f);
-    }
     const float mx = fmaxf(fmaxf(p[0].x, p[1].x), fmaxf(p[2].x, p[3].x));  // finite: the tile's first token exists
     float sum = 0.f;
 #pragma unroll
@@ -66,44 +59,16 @@ __device__ inline void merge_tile_partials(const HeadArgs& a, const float2* lp, 
   }
 }
 
-// x_k = max(x_k, x_k rotated right by N lanes inside its row of 16), for eight registers that do not depend on one
-// another, in one statement: the two wait states a DPP read needs after a vector write of its source are paid once
-// in front, not once per instruction.
-template <int N>
-__device__ inline void max_ror_x8(float* x) {
-  static_assert(N == 1 || N == 2 || N == 4 || N == 8, "rotation inside a row of 16 lanes");
-  asm("s_nop 1\n\t"
-      "v_max_f32_dpp %0, %0, %0 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
-      "v_max_f32_dpp %1, %1, %1 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
-      "v_max_f32_dpp %2, %2, %2 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
-      "v_max_f32_dpp %3, %3, %3 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
-      "v_max_f32_dpp %4, %4, %4 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
-      "v_max_f32_dpp %5, %5, %5 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
-      "v_max_f32_dpp %6, %6, %6 row_ror:%8 row_mask:0xf bank_mask:0xf\n\t"
-      "v_max_f32_dpp %7, %7, %7 row_ror:%8 row_mask:0xf bank_mask:0xf"
-      : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
-      : "n"(N));
-}
-// max of finite numbers in one instruction (fmaxf also quiets signalling NaNs, which costs a second one)
-__device__ inline float vmax(float x, float y) {
-  float r;
-  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
-  return r;
-}
-__device__ inline float vmax3(float x, float y, float z) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
-  return r;
-}
-
 // Epilogue of a wavefront that holds a whole 128 x 128 tile (four wavefronts per workgroup), interior tiles only:
 // rows mw .. mw + 127 all exist, tokens vbase .. vbase + 127 all exist.  With one wavefront per SIMD nothing else
-// runs while it does, so what counts is the number of instructions, of any kind.  Against two calls of the shared
-// 128 x 64 epilogue: one reduction per row over its 128 tokens instead of two over 64 (a lane holds four tokens of
-// a row: the first three steps are in its own registers), one running pointer per row for the four stores, the
-// partial straight to LDS (the second 64-token slot of the pair stays unwritten: the caller tells the merge so),
-// and the wait states of the DPP steps paid once per eight.
-// lp: this wavefront's first partial slot in LDS, [row][4 slots] of float2.
+// runs while it does, so what counts is the number of instructions, of any kind, and every wait for a result.
+// Against two calls of the shared 128 x 64 epilogue: a lane holds four tokens of a row, so the first steps of a
+// row's reduction are in its own registers; the reduction stops at the row of 16 lanes (the DPP steps), and each
+// of the two rows of 16 that share a matrix row writes the partial of its own 64 tokens (tokens j, j + 32, j + 64,
+// j + 96 of the 128, j < 16 or j >= 16: any split of the tile's tokens will do for the merge that follows), so
+// nothing crosses between the rows of 16 and nothing waits for the LDS crossbar; one running pointer per row for
+// the four stores; the wait states of the DPP steps paid once per eight.
+// lp: this wavefront's first partial slot in LDS, [row][4 slots] of float2; the wavefront fills two slots per row.
 template <bool CE>
 __device__ __forceinline__ void epilogue_128x128(const HeadArgs& a, floatx16 (&acc)[2][4][2], int mw, int vbase, int lane,
                                                  float2* lp) {
@@ -130,7 +95,7 @@ __device__ __forceinline__ void epilogue_128x128(const HeadArgs& a, floatx16 (&a
       }
     }
   }
-  float2* pw = lp + 4 * h * 4;
+  float2* pw = lp + 4 * h * 4 + ((lane >> 4) & 1);
   // Each phase runs over eight rows before the next begins (the scheduling barriers keep it so: left alone, the
   // compiler finishes one row's chain before it starts the next, every step waiting for the one before), so
   // neighbours in program order never depend on one another.
@@ -138,7 +103,7 @@ __device__ __forceinline__ void epilogue_128x128(const HeadArgs& a, floatx16 (&a
   for (int g = 0; g < 8; ++g) {
     const int i = g >> 1, r0 = (g & 1) * 8;  // 32-row tile, first accumulator index
     const int mr0 = i * 32 + 8 * (r0 >> 2);  // row of index r0 (before the 4 h of the half-wavefront)
-    float l[8][4], m[8], e[8], t[8];
+    float l[8][4], m[8], e[8], t[8];  // t: -max log2(e)
 #pragma unroll
     for (int q = 0; q < 8; ++q)
 #pragma unroll
@@ -170,12 +135,6 @@ __device__ __forceinline__ void epilogue_128x128(const HeadArgs& a, floatx16 (&a
     max_ror_x8<1>(m);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) t[q] = swap16(m[q]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int q = 0; q < 8; ++q) m[q] = vmax(m[q], t[q]);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
     for (int q = 0; q < 8; ++q) t[q] = m[q] * -kLog2e;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -202,13 +161,9 @@ __device__ __forceinline__ void epilogue_128x128(const HeadArgs& a, floatx16 (&a
 #pragma unroll
     for (int q = 0; q < 8; ++q) e[q] += row_ror<1>(e[q]);
     __builtin_amdgcn_sched_barrier(0);
+    // every lane of a row of 16 holds the pair of its 64 tokens and writes it to the same address
 #pragma unroll
-    for (int q = 0; q < 8; ++q) t[q] = swap16(e[q]);
-    __builtin_amdgcn_sched_barrier(0);
-    // every lane of a half-wavefront holds its row's pair and writes it to the same address
-#pragma unroll
-    for (int q = 0; q < 8; ++q)
-      pw[(mr0 + 8 * (q >> 2) + (q & 3)) * 4] = make_float2(m[q], e[q] + t[q]);
+    for (int q = 0; q < 8; ++q) pw[(mr0 + 8 * (q >> 2) + (q & 3)) * 4] = make_float2(m[q], e[q]);
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -575,7 +530,6 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
     }
   };
   float2* lp = reinterpret_cast<float2*>(ringH);
-  int* wide = reinterpret_cast<int*>(lp + BM * 4);  // behind the partials; an idle wavefront's rows are not merged
   if (idle) {
     walk(std::true_type{});
     lds_barrier();
@@ -585,9 +539,7 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
     for (int i = 0; i < 4; ++i) mfma_row(cur, i);  // last slice of the last step
     lds_barrier();  // nobody reads the rings any more: the H ring takes the partials
     const int mw = m0 + wm * 128, vb = n0 + wn * 128;
-    const bool interior = mw + 128 <= M && vb + 128 <= a.V;  // wavefront-uniform
-    if (lane == 0) wide[wave] = interior;
-    if (interior) {
+    if (mw + 128 <= M && vb + 128 <= a.V) {  // wavefront-uniform
       epilogue_128x128<CE>(a, acc, mw, vb, lane, lp + wm * 128 * 4 + 2 * wn);
     } else {
       store_logits_and_partials<4, CE>(a, acc[0], mw, vb, M, lane, lp, wm * 128, 2 * wn);
@@ -595,7 +547,7 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
     }
   }
   lds_barrier();
-  merge_tile_partials(a, lp, m0, nt, M, tid, wide);
+  merge_tile_partials(a, lp, m0, nt, M, tid);
 }
 
 }  // namespace
