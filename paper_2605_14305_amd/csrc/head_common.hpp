@@ -149,29 +149,31 @@ __device__ inline float vmax3(float x, float y, float z) {
 // CE = true is the cross-entropy use of the head: nothing is written but the partials and, for
 // the lane that holds a row's label token, that token's scaled logit.
 //
-// lds_part != nullptr: the partials do not go to memory but to LDS, [row of the workgroup tile][4 token
-// groups of 64], for the caller to merge into one partial per (row, workgroup tile); mw_local is the
-// wavefront's first row inside the workgroup tile and lcol its token group.  A wavefront whose tokens all
-// lie past V then leaves (-inf, 0).
+// The partials do not go to memory but to LDS, lds_part[row of the workgroup tile][4 token groups of 64], for the
+// caller to merge into one partial per (row, workgroup tile); mw_local is the wavefront's first row inside the
+// workgroup tile and lcol its token group.  A wavefront whose tokens all lie past V leaves (-inf, 0).  (The pointer
+// is typed as LDS: through a generic pointer the writes would be FLAT instructions, which count in the
+// vector-memory counter too and complete out of its order, and the kernels that call this with loads in flight
+// wait by count.)
 template <int NI, bool CE = false, int RB = 16>
 __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, floatx16 (&acc)[NI][2], int mw, int vbase,
-                                                 int M, int lane, float2* lds_part = nullptr, int mw_local = 0,
-                                                 int lcol = 0) {
+                                                 int M, int lane, float2* lds_part, int mw_local, int lcol) {
   static_assert(RB == 4 || RB == 8 || RB == 16, "accumulator indices per batch");
   constexpr float kLog2e = 1.4426950408889634f;
   const int j32 = lane & 31, h = lane >> 5;
   const float sc = a.inv_tau;
-  const int ptile = vbase / kTiledTn;
   const int v0 = vbase + j32, v1 = v0 + 32;
   float* lbase = CE ? nullptr : a.logits + (size_t)(mw + 4 * h) * a.ldl + v0;
-  float2* pbase = lds_part ? lds_part + (mw_local + 4 * h) * 4 + lcol : a.partials + (size_t)(mw + 4 * h) * a.nT + ptile;
-  const size_t pstride = lds_part ? 4 : (size_t)a.nT;
-  if (lds_part && vbase >= a.V) {
+  typedef float floatx2 __attribute__((ext_vector_type(2)));  // float2's layout, assignable in any address space
+  typedef __attribute__((address_space(3))) floatx2 lds_floatx2;
+  lds_floatx2* pbase = (lds_floatx2*)lds_part + (mw_local + 4 * h) * 4 + lcol;
+  constexpr int pstride = 4;
+  if (vbase >= a.V) {
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (j32 == 0) pbase[(i * 32 + 8 * (r >> 2) + (r & 3)) * pstride] = make_float2(-INFINITY, 0.f);
+        if (j32 == 0) pbase[(i * 32 + 8 * (r >> 2) + (r & 3)) * pstride] = floatx2{-INFINITY, 0.f};
     return;
   }
   if constexpr (CE) {
@@ -253,7 +255,7 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
         for (int q = 0; q < RB; ++q) {
           const int r = rb + q;
           const int mr = i * 32 + 8 * (r >> 2) + (r & 3);
-          pbase[(size_t)mr * pstride] = make_float2(mx[q], e[q] + t[q]);
+          pbase[mr * pstride] = floatx2{mx[q], e[q] + t[q]};
         }
       }
     }
@@ -277,9 +279,27 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
         float e = (ok0 ? exp2f(fmaf(l0, kLog2e, -mb)) : 0.f) + (ok1 ? exp2f(fmaf(l1, kLog2e, -mb)) : 0.f);
         e = row16_sum(e);
         e += swap16(e);
-        if (j32 == 0 && (row_ok || lds_part)) pbase[(size_t)mr * pstride] = make_float2(row_ok ? mx : -INFINITY, row_ok ? e : 0.f);
+        if (j32 == 0) pbase[mr * pstride] = floatx2{row_ok ? mx : -INFINITY, row_ok ? e : 0.f};
       }
     }
+  }
+}
+
+// One (max, sum exp) partial per (row, workgroup tile of 256 tokens): the four partials of a row that the epilogue
+// left in LDS ([row of the tile][4 slots], each over a quarter of the tile's tokens; which quarter is the epilogue's
+// business), merged in a fixed order by the thread that owns the row.  A quarter of the partials for the kernels
+// that read them next.  rows: rows of the workgroup tile; m0: its first row; nt: its 256-token tile.
+__device__ inline void merge_tile_partials(const HeadArgs& a, const float2* lp, int rows, int m0, int nt, int M, int tid) {
+  constexpr float kLog2e = 1.4426950408889634f;
+  if (tid < rows && m0 + tid < M) {
+    float2 p[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) p[c] = lp[tid * 4 + c];
+    const float mx = fmaxf(fmaxf(p[0].x, p[1].x), fmaxf(p[2].x, p[3].x));  // finite: the tile's first token exists
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sum += p[c].y * exp2f((p[c].x - mx) * kLog2e);
+    a.partials[(size_t)(m0 + tid) * a.nT + nt] = make_float2(mx, sum);
   }
 }
 

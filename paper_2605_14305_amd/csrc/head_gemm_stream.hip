@@ -4,13 +4,14 @@
 // built around streaming W without a pause.
 //
 // One persistent workgroup per CU takes the 256-token tiles b, b + G, ... and walks k in steps of
-// 32 over all of them as ONE sequence of steps: W goes through a ring of eight 16 KB LDS stages
-// filled by direct-to-LDS loads seven steps ahead (measured: a lead of three steps does as well;
+// 32 over all of them as ONE sequence of steps: W goes through a ring of seven (eight with 64-row tiles) 16 KB LDS
+// stages filled by direct-to-LDS loads six (seven) steps ahead (measured: a lead of three steps does as well;
 // a wavefront with more loads outstanding than the memory pipeline takes blocks at its next load
 // instruction, and that, not a wait for data, is where the loading wavefronts spend a third of
 // their time), H, which every workgroup re-reads and which therefore sits in L2, through a ring
-// of four 8 KB stages three steps ahead.  Together they use the whole 160 KB of LDS.  The loads run on across tile boundaries, so only the first
-// tile of a workgroup pays the cold start, and the epilogue of a tile (registers only, no LDS)
+// of four 8 KB stages three steps ahead.  With 4 KB for the partials of a finished tile that is
+// 148 of the 160 KB of LDS.  The loads run on across tile boundaries, so only the first
+// tile of a workgroup pays the cold start, and the epilogue of a tile (registers, and 4 KB of LDS of its own)
 // runs while the first stages of the next tile arrive.  The vector-memory counter of a wavefront
 // completes in order, so two different leads cannot share a wavefront: wavefronts 0..3 load W
 // (four 1 KB loads per step each), wavefronts 4..7 load H (two per step each).  The stores of an
@@ -39,8 +40,8 @@ namespace fef {
 namespace {
 
 constexpr int SM = 128, SN = 256, SK = 32;     // SM: rows of the largest tile
-constexpr int kRingW = 8, kRingH = 4;          // stages; loads run kRing - 1 k-steps ahead
-constexpr int kStageW = SN * 4, kStageH = SM * 4;  // 16-byte chunks per stage
+constexpr int kRingH = 4;                      // stages; loads run kRing - 1 k-steps ahead
+constexpr int kStageW = SN * 4;                // 16-byte chunks per W stage
 constexpr int kLoadsW = 4;                     // load instructions per W-loading wavefront per stage
 
 template <int NI>
@@ -52,8 +53,13 @@ struct Frag {
 template <int NI, bool CE>
 __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tiles) {
   constexpr int kLoadsH = NI;                 // 16 rows per load, 16 NI rows per H-loading wavefront
-  __shared__ bf16x8 ringW[kRingW * kStageW];  // 128 KB
-  __shared__ bf16x8 ringH[kRingH * kStageH];  // 32 KB (half used when NI = 1): one workgroup per CU
+  // 64-row tiles leave room for an eighth W stage (8 x 16 + 4 x 4 + 4 = 148 KB; 128-row tiles: 7 x 16 + 4 x 8 + 4),
+  // and with it the head is 6 us faster at M = 64 than with seven
+  constexpr int kRingW = NI == 1 ? 8 : 7;
+  constexpr int kStageH = 64 * NI * 4;        // 16-byte chunks per H stage
+  __shared__ bf16x8 ringW[kRingW * kStageW];
+  __shared__ bf16x8 ringH[kRingH * kStageH];  // one workgroup per CU
+  __shared__ float2 lpart[SM * 4];            // 4 KB: the four 64-token partials of each row of a tile, to be merged
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;  // row half, token column
@@ -210,12 +216,20 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
     int sw = 0, sh = 0;               // stages of the current step in the two rings
     int tile_c = blockIdx.x, kc = 0;  // compute cursor
     auto next_stage = [&]() {
-      sw = (sw + 1) & (kRingW - 1);
+      sw = sw + 1 == kRingW ? 0 : sw + 1;
       sh = (sh + 1) & (kRingH - 1);
     };
-    auto end_of_step = [&]() {  // tile finished: epilogue from the registers, next tile starts at zero
+    // Tile finished: epilogue from the registers, next tile starts at zero.  The four 64-token partials of a row
+    // (one per wavefront column) meet in LDS and leave as one partial per (row, 256-token tile): a quarter of the
+    // partials for the kernels that follow (step 261 -> 256 us at M = 128; at M = 64 what the next kernel gains the
+    // head loses).  Every wavefront, whatever it loads, finishes its tiles at the same steps, so the barrier is met
+    // by all; the next tile's partials are written at least two step barriers later.  (Leaving the merge to the
+    // next step's barrier instead of one of its own measured the same.)
+    auto end_of_step = [&]() {
       if (++kc == nk) {
-        store_logits_and_partials<NI, CE>(a, acc, wm * (32 * NI), tile_c * SN + wn * 64, M, lane);
+        store_logits_and_partials<NI, CE, 8>(a, acc, wm * (32 * NI), tile_c * SN + wn * 64, M, lane, lpart, wm * (32 * NI), wn);
+        lds_barrier();
+        merge_tile_partials(a, lpart, 64 * NI, 0, tile_c, M, tid);
         clear_acc();
         kc = 0;
         tile_c += G;

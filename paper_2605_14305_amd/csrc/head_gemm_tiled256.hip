@@ -42,23 +42,6 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kStage = BM * 8;   // 16-byte chunks per operand stage (BM == BN)
 constexpr int kRingH = 2, kRingW = 3;
 
-// One (max, sum exp) partial per (row, workgroup tile of 256 tokens): the four partials of a row that the epilogue
-// left in LDS (each over a quarter of the tile's tokens; which quarter is the epilogue's business), merged in a
-// fixed order by the thread that owns the row.  A quarter of the partials for the kernels that read them next.
-__device__ inline void merge_tile_partials(const HeadArgs& a, const float2* lp, int m0, int nt, int M, int tid) {
-  constexpr float kLog2e = 1.4426950408889634f;
-  if (tid < BM && m0 + tid < M) {
-    float2 p[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) p[c] = lp[tid * 4 + c];
-    const float mx = fmaxf(fmaxf(p[0].x, p[1].x), fmaxf(p[2].x, p[3].x));  // finite: the tile's first token exists
-    float sum = 0.f;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) sum += p[c].y * exp2f((p[c].x - mx) * kLog2e);
-    a.partials[(size_t)(m0 + tid) * a.nT + nt] = make_float2(mx, sum);
-  }
-}
-
 // Epilogue of a wavefront that holds a whole 128 x 128 tile (four wavefronts per workgroup), interior tiles only:
 // rows mw .. mw + 127 all exist, tokens vbase .. vbase + 127 all exist.  With one wavefront per SIMD nothing else
 // runs while it does, so what counts is the number of instructions, of any kind, and every wait for a result.
@@ -355,7 +338,7 @@ __global__ __launch_bounds__(512) void head_tiled256_kernel(HeadArgs a, int m_ti
   float2* lp = reinterpret_cast<float2*>(ringH);
   if (!idle) store_logits_and_partials<4, CE>(a, acc, m0 + wm * 128, n0 + wn * 64, M, lane, lp, wm * 128, wn);
   lds_barrier();
-  merge_tile_partials(a, lp, m0, nt, M, tid);
+  merge_tile_partials(a, lp, BM, m0, nt, M, tid);
 }
 
 
@@ -547,7 +530,7 @@ __global__ __launch_bounds__(256) void head_tiled256w4_kernel(HeadArgs a, int m_
     }
   }
   lds_barrier();
-  merge_tile_partials(a, lp, m0, nt, M, tid);
+  merge_tile_partials(a, lp, BM, m0, nt, M, tid);
 }
 
 }  // namespace
