@@ -221,8 +221,7 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
     };
     // Tile finished: epilogue from the registers, next tile starts at zero.  The four 64-token partials of a row
     // (one per wavefront column) meet in LDS and leave as one partial per (row, 256-token tile): a quarter of the
-    // partials for the kernels that follow (step 261 -> 256 us at M = 128; at M = 64 what the next kernel gains the
-    // head loses).  Every wavefront, whatever it loads, finishes its tiles at the same steps, so the barrier is met
+    // partials for the kernels that follow (step 261 -> 256 us at M = 128, 1 to 2 us at M = 64).  Every wavefront, whatever it loads, finishes its tiles at the same steps, so the barrier is met
     // by all; the next tile's partials are written at least two step barriers later.  (Leaving the merge to the
     // next step's barrier instead of one of its own measured the same.)
     auto end_of_step = [&]() {
