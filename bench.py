@@ -52,15 +52,17 @@ class HipEvents:
         self.hip.hipEventDestroy(e)
 
 
-def head_bytes(wl, skinny, M, rowstream=False, tiled256=False):
+def head_bytes(wl, skinny, M, rowstream=False, tiled256=False, stream=False):
     """Algorithmic HBM bytes of one vocabulary-head launch over M rows: W once, H once, fp32
     logits written once, the per-tile (max, sum exp) partials."""
     esz = 2 if wl.dtype == "bf16" else 4
     nT = min(-(-wl.V // 16), 256) if skinny else -(-wl.V // 64)
     if tiled256:
-        nT = -(-wl.V // 256)      # the 256 x 256 and LDS-streaming kernels merge their partials per 256-token tile
+        nT = -(-wl.V // 256)      # the 256 x 256 kernels merge their partials per workgroup tile
     if rowstream:
         nT = min(256, -(-(-(-wl.V // 16)) // 8))
+    if stream:
+        nT = min(256, -(-(-(-wl.V // 64)) // 4))   # the LDS-streaming kernel leaves one partial per row and workgroup
     return wl.V * wl.d * esz + M * wl.d * esz + M * wl.V * 4 + M * nT * 8
 
 
@@ -160,7 +162,7 @@ def bench_cross_entropy(args, wl, W, Wd, dev):
     elapsed = time.perf_counter() - t0
     head_s = sum(ev.elapsed_ms(a, b) for a, b in pairs) / len(pairs) / 1e3
     esz = 2 if wl.dtype == "bf16" else 4
-    nT = -(-wl.V // 256)          # the kernels this call uses merge their partials per 256-token tile
+    nT = min(256, -(-(-(-wl.V // 64)) // 4)) if R <= 128 else -(-wl.V // 256)   # per workgroup / per 256-token tile
     hb = wl.V * wl.d * esz + R * wl.d * esz + R * nT * 8 + R * 4       # no logits are written
     flops = 2.0 * R * wl.V * wl.d
     if hb / (HBM_PEAK_GBS * 1e9) >= flops / (MFMA_BF16_PEAK_TFLOPS * 1e12):
@@ -380,7 +382,7 @@ def time_verify(args, wl, Wd, dev, steps, warmup):
     positions = wl.B * wl.K
     M = positions if args.split else 2 * positions   # rows through one head launch
     hb = head_bytes(wl, variant == fb.FEF_GEMM_SKINNY, M, variant == fb.FEF_GEMM_ROWSTREAM,
-                    variant in (fb.FEF_GEMM_TILED256, fb.FEF_GEMM_STREAM))
+                    variant == fb.FEF_GEMM_TILED256, variant == fb.FEF_GEMM_STREAM)
     flops = 2.0 * M * wl.V * wl.d
     hbm_time, mfma_time = hb / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if hbm_time >= mfma_time:

@@ -131,7 +131,12 @@ fef_status make_layout(const fef_params* p, int32_t K, int32_t block, Layout* L)
     L->tile_unit = fef::kSkinnyUnit;
     L->tile_T = (p->V + fef::kSkinnyUnit - 1) / fef::kSkinnyUnit;
     L->nT = fef::rowstream_grid(p->V);
-  } else if (L->variant == FEF_GEMM_TILED256 || L->variant == FEF_GEMM_STREAM) {
+  } else if (L->variant == FEF_GEMM_STREAM) {
+    // one partial per (row, workgroup); a workgroup's tokens are a contiguous run of 64-token units
+    L->tile_unit = fef::kTiledTn;
+    L->tile_T = (p->V + fef::kTiledTn - 1) / fef::kTiledTn;
+    L->nT = fef::stream_grid(p->V);
+  } else if (L->variant == FEF_GEMM_TILED256) {
     // one partial per (row, workgroup tile of 256 tokens)
     L->tile_unit = fef::kTiled256Tn;
     L->tile_T = L->nT = (p->V + fef::kTiled256Tn - 1) / fef::kTiled256Tn;
@@ -430,8 +435,9 @@ fef_status ce_check(const fef_params* p, int32_t R, int* variant, int* nT, size_
       return fail(FEF_ERR_UNSUPPORTED, "cross-entropy runs through the F32, STREAM or TILED256 head kernel");
   }
   *variant = v;
-  *nT = v == FEF_GEMM_TILED256 || v == FEF_GEMM_STREAM ? (p->V + fef::kTiled256Tn - 1) / fef::kTiled256Tn
-                                                       : (p->V + fef::kTiledTn - 1) / fef::kTiledTn;
+  *nT = v == FEF_GEMM_STREAM     ? fef::stream_grid(p->V)
+        : v == FEF_GEMM_TILED256 ? (p->V + fef::kTiled256Tn - 1) / fef::kTiled256Tn
+                                 : (p->V + fef::kTiledTn - 1) / fef::kTiledTn;
   *total = align_up((size_t)R * (size_t)*nT * sizeof(float2), 256) + align_up((size_t)R * sizeof(float), 256);
   return FEF_OK;
 }

@@ -68,14 +68,15 @@ struct HeadArgs {
 constexpr int kSkinnyUnit = 16;     // the skinny kernel walks W in tiles of 16 tokens ...
 constexpr int kSkinnyMaxGrid = 256;  // ... split evenly over at most one workgroup per CU, and
                                      // writes one partial per (row, workgroup)
-constexpr int kTiledTn = 64;         // partial-tile width of the tiled and f32 kernels
-constexpr int kTiled256Tn = 256;     // ... of the 256 x 256 and LDS-streaming kernels (merged through LDS in their epilogue)
+constexpr int kTiledTn = 64;         // partial-tile width of the tiled and f32 kernels, share unit of the LDS-streaming kernel
+constexpr int kTiled256Tn = 256;     // ... of the 256 x 256 kernels (merged through LDS in their epilogue)
 
 bool skinny_supports(int M, int d);
 hipError_t launch_head_skinny(const HeadArgs& a);
 hipError_t launch_head_tiled(const HeadArgs& a);
 hipError_t launch_head_tiled256(const HeadArgs& a);
 bool stream_supports(int M, int d);
+int stream_grid(int V);     // workgroups = partial slots per row
 hipError_t launch_head_stream(const HeadArgs& a);
 bool rowstream_supports(int M, int d);
 int rowstream_grid(int V);  // workgroups = partial slots per row

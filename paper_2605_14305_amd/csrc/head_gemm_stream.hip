@@ -3,7 +3,7 @@
 // the cost (2 M V d flops need well under the time 1 GB of W takes from HBM), so the kernel is
 // built around streaming W without a pause.
 //
-// One persistent workgroup per CU takes the 256-token tiles b, b + G, ... and walks k in steps of
+// One persistent workgroup per CU takes an equal share of the vocabulary as 256-token tiles and walks k in steps of
 // 32 over all of them as ONE sequence of steps: W goes through a ring of seven (eight with 64-row tiles) 16 KB LDS
 // stages filled by direct-to-LDS loads six (seven) steps ahead (measured: a lead of three steps does as well;
 // a wavefront with more loads outstanding than the memory pipeline takes blocks at its next load
@@ -31,7 +31,6 @@
 // access pattern gets 4.5 TB/s in step and 5.4 to 6.3 TB/s with staggered starts.
 //
 // LDS stages are [rows][4 chunks of 16 B], chunks swizzled as in the 256 x 256 kernel.
-#include <atomic>
 #include <type_traits>
 
 #include "head_common.hpp"
@@ -51,7 +50,7 @@ struct Frag {
 
 // NI = 32-row tiles per wavefront: the workgroup tile has 64 NI rows.
 template <int NI, bool CE>
-__global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tiles) {
+__global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a_in, int n_units) {
   constexpr int kLoadsH = NI;                 // 16 rows per load, 16 NI rows per H-loading wavefront
   // 64-row tiles leave room for an eighth W stage (8 x 16 + 4 x 4 + 4 = 148 KB; 128-row tiles: 7 x 16 + 4 x 8 + 4),
   // and with it the head is 6 us faster at M = 64 than with seven
@@ -64,10 +63,18 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;  // row half, token column
   const int j32 = lane & 31, h = lane >> 5;
-  const int M = a.nrows;
+  const int M = a_in.nrows;
+  // This workgroup's tokens: units [u0, u1) of 64 tokens, an equal share of the vocabulary (a share of whole
+  // 256-token tiles leaves the 594 tiles of a 151936-token vocabulary as three tiles for 82 workgroups and two for
+  // the rest, and everybody waits for the 82; the kernel's time goes with the bytes a workgroup reads, and a last
+  // tile of one to three 64-token columns reads that much less of W).  To the kernel the vocabulary ends where
+  // the share ends: rows of W past it re-read the share's last row and are masked in the epilogue.
   const int G = gridDim.x;
+  const int u0 = (int)((long)blockIdx.x * n_units / G), u1 = (int)((long)(blockIdx.x + 1) * n_units / G);
+  HeadArgs a = a_in;
+  a.V = min(a_in.V, u1 * 64);
   const int nk = a.d / SK;
-  const int my_tiles = (n_tiles - (int)blockIdx.x + G - 1) / G;
+  const int my_tiles = (u1 - u0 + 3) / 4;
   const int T = my_tiles * nk;  // steps of this workgroup; even, because nk is
 
   floatx16 acc[NI][2];
@@ -143,11 +150,11 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
     // k-step (k0 + t) mod nk, in both roles.
     const int k0 = (int)((blockIdx.x * 37u) % (unsigned)nk);
     // loader cursor: the next step to load is k-step kl of tile tile_l and goes to stage s_load
-    int tile_l = blockIdx.x, kl = 0, s_load = 0, t_load = 0;
+    int tile_l = 0, kl = 0, s_load = 0, t_load = 0;  // tiles count from the share's first token
     auto retarget = [&]() {  // gp[] at the first k-step of tile tile_l
 #pragma unroll
       for (int n = 0; n < NL; ++n)
-        gp[n] = (W_ROLE ? (const __bf16*)a.W + (size_t)min(tile_l * SN + lrow[n], a.V - 1) * a.d
+        gp[n] = (W_ROLE ? (const __bf16*)a.W + (size_t)min(u0 * 64 + tile_l * SN + lrow[n], a.V - 1) * a.d
                         : h_row(a, min(lrow[n], M - 1))) + lchunk[n] + k0 * SK;
     };
     retarget();
@@ -180,7 +187,7 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
       ++t_load;
       if (++kl == nk) {
         kl = 0;
-        tile_l += G;
+        tile_l += 1;
         if (t_load < T) retarget();
       } else if (kl == nk - k0) {  // back to k = 0
 #pragma unroll
@@ -214,24 +221,37 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
     Frag<NI> f0, f1;
     read_frag(0, 0, f0);
     int sw = 0, sh = 0;               // stages of the current step in the two rings
-    int tile_c = blockIdx.x, kc = 0;  // compute cursor
+    int tile_c = 0, kc = 0;  // compute cursor
+    float run_mx = -INFINITY, run_sum = 0.f;  // thread tid < 64 NI: (max, sum exp) of row tid over the tiles done so far
     auto next_stage = [&]() {
       sw = sw + 1 == kRingW ? 0 : sw + 1;
       sh = (sh + 1) & (kRingH - 1);
     };
     // Tile finished: epilogue from the registers, next tile starts at zero.  The four 64-token partials of a row
-    // (one per wavefront column) meet in LDS and leave as one partial per (row, 256-token tile): a quarter of the
-    // partials for the kernels that follow (step 261 -> 256 us at M = 128, 1 to 2 us at M = 64).  Every wavefront, whatever it loads, finishes its tiles at the same steps, so the barrier is met
-    // by all; the next tile's partials are written at least two step barriers later.  (Leaving the merge to the
-    // next step's barrier instead of one of its own measured the same.)
+    // (one per wavefront column) meet in LDS, where the thread that owns the row folds them into its running
+    // partial; the workgroup leaves ONE partial per row, over all its tokens, at the end: 256 partials per row for
+    // the kernels that follow.  Every wavefront, whatever it loads, finishes its tiles at the same steps, so the
+    // barrier is met by all; the next tile's partials are written at least two step barriers later.
     auto end_of_step = [&]() {
       if (++kc == nk) {
-        store_logits_and_partials<NI, CE, 8>(a, acc, wm * (32 * NI), tile_c * SN + wn * 64, M, lane, lpart, wm * (32 * NI), wn);
+        store_logits_and_partials<NI, CE, 8>(a, acc, wm * (32 * NI), u0 * 64 + tile_c * SN + wn * 64, M, lane, lpart,
+                                             wm * (32 * NI), wn);
         lds_barrier();
-        merge_tile_partials(a, lpart, 64 * NI, 0, tile_c, M, tid);
+        if (tid < 64 * NI && tid < M) {
+          constexpr float kLog2e = 1.4426950408889634f;
+          float2 p[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) p[c] = lpart[tid * 4 + c];
+          const float mx = fmaxf(fmaxf(run_mx, p[0].x), fmaxf(fmaxf(p[1].x, p[2].x), p[3].x));  // finite: the tile's first token exists
+          float sum = run_sum * exp2f((run_mx - mx) * kLog2e);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) sum += p[c].y * exp2f((p[c].x - mx) * kLog2e);
+          run_mx = mx;
+          run_sum = sum;
+        }
         clear_acc();
         kc = 0;
-        tile_c += G;
+        tile_c += 1;
       }
     };
     // Steady-state step t (t + LEAD < T): on entry `cur` holds the fragments of stage t.
@@ -301,6 +321,7 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
       step_tail(t, f0, f1);
       step_tail(t + 1, f1, f0);
     }
+    if (tid < 64 * NI && tid < M) a.partials[(size_t)tid * a.nT + blockIdx.x] = make_float2(run_mx, run_sum);
   };
   if (wave < 4) run(std::integral_constant<int, 0>{});
   else run(std::integral_constant<int, 1>{});
@@ -310,31 +331,23 @@ __global__ __launch_bounds__(512) void head_stream_kernel(HeadArgs a, int n_tile
 
 bool stream_supports(int M, int d) { return M <= SM && d % 64 == 0; }
 
+// One workgroup per CU of a 256-CU device (the kernel uses most of a CU's LDS), fewer when the vocabulary has fewer
+// than 256 tiles of 256 tokens; workgroup b takes units floor(b U / G) .. floor((b + 1) U / G) of 64 tokens.
+int stream_grid(int V) {
+  const int units = (V + 63) / 64, want = (units + 3) / 4;
+  return want < kSkinnyMaxGrid ? want : kSkinnyMaxGrid;
+}
+
 template <int NI>
-static void launch_stream(const HeadArgs& a, int grid, int n_tiles) {
-  if (a.labels) FEF_LAUNCH_HEAD((head_stream_kernel<NI, true>), dim3((unsigned)grid), dim3(512), a, a, n_tiles);
-  else FEF_LAUNCH_HEAD((head_stream_kernel<NI, false>), dim3((unsigned)grid), dim3(512), a, a, n_tiles);
+static void launch_stream(const HeadArgs& a, int grid, int n_units) {
+  if (a.labels) FEF_LAUNCH_HEAD((head_stream_kernel<NI, true>), dim3((unsigned)grid), dim3(512), a, a, n_units);
+  else FEF_LAUNCH_HEAD((head_stream_kernel<NI, false>), dim3((unsigned)grid), dim3(512), a, a, n_units);
 }
 
 hipError_t launch_head_stream(const HeadArgs& a) {
-  const int n_tiles = (a.V + SN - 1) / SN;
-  // one workgroup per CU (the kernel uses all of a CU's LDS); each walks its tiles back to back
-  static std::atomic<int> cus[64];  // CU count per device, 0 = not asked yet; callers may be concurrent threads
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  int n_cu = cus[dev].load(std::memory_order_relaxed);
-  if (n_cu == 0) {
-    int n = 0;
-    e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
-    n_cu = n > 0 ? n : 1;
-    cus[dev].store(n_cu, std::memory_order_relaxed);
-  }
-  const int grid = n_tiles < n_cu ? n_tiles : n_cu;
-  if (a.nrows <= 64) launch_stream<1>(a, grid, n_tiles);
-  else launch_stream<2>(a, grid, n_tiles);
+  const int n_units = (a.V + 63) / 64, grid = stream_grid(a.V);
+  if (a.nrows <= 64) launch_stream<1>(a, grid, n_units);
+  else launch_stream<2>(a, grid, n_units);
   return hipGetLastError();
 }
 

@@ -258,7 +258,8 @@ __device__ inline int row_argmax(const VerifyArgs& a, const float2* P, const flo
 }
 
 constexpr int kChunkPer = 16;  // residual chunks per lane in the one-wavefront final phase
-constexpr int kTilePer = 8;  // tokens per lane inside one partial tile: tiles of up to 512 tokens
+constexpr int kTilePer = 10;  // tokens per lane inside one partial tile: tiles of up to 640 tokens (a 151936-token
+                              // vocabulary over 256 workgroups: 576 to 640 tokens each), longer ones are re-read
 
 // ---------------------------------------------------------------------------------------------
 // Kernel 1: per-row log-sum-exp, window slot, draft sample.  One wavefront per row.

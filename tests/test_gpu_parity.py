@@ -251,6 +251,15 @@ def test_very_large_vocabulary_generic_partial_merge():
     assert st["near_flipped"] == 0 and st["equal"] == 2
 
 
+@pytest.mark.parametrize("B,K,d,variant", [(1, 8, 512, fb.FEF_GEMM_SKINNY), (5, 8, 64, fb.FEF_GEMM_STREAM)])
+def test_workgroup_shares_of_more_than_640_tokens(B, K, d, variant):
+    """One partial per row and workgroup over its contiguous share of the vocabulary (the kernels up to 32 rows, the
+    LDS-streaming kernel): with 170003 tokens over 256 workgroups a share has 656 to 672 tokens, more than the
+    draft sampler keeps in registers, so the selected share is re-read from the logits."""
+    ref, out, st = run_case(B, K, 16, d, 170003, seed=15, rho=0.8, variant=variant, with_logits=False)
+    assert st["near_flipped"] <= B // 20 and st["equal"] + st["near_margin"] >= B
+
+
 def test_skinny_and_tiled_agree():
     W = synth.make_head(3000, 512, 5)
     hidden = synth.make_hidden(1, 8, 512, 5, 0.7, 3.0 / (0.02 * np.sqrt(512)))
