@@ -177,25 +177,34 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
     return;
   }
   if constexpr (CE) {
-    // The label token's logit of a row lies in exactly one lane of one wavefront.  Most calls
-    // hold none (64 of V tokens, 32 NI rows): every lane looks up one or two of the rows' labels,
-    // and only a wavefront that finds one inside its 64 tokens goes through its elements.
-    bool hit = false;
+    // The label token's logit of a row lies in exactly one lane of one wavefront.  Most calls hold none (64 of V
+    // tokens, 32 NI rows): every lane looks up one or two of the rows' labels, and a label that falls among this
+    // call's tokens is fetched in a loop over the hits with wavefront-uniform indices (the 32 x 32 accumulator tile
+    // and the element inside it by comparison of scalars; the lane that holds it stores it).  Going through all of a
+    // lane's elements with a label lookup each is a chain of load latencies per hit, and the workgroup that pays it
+    // falls out of step with those it shares operand tiles with through L2.
 #pragma unroll
-    for (int r0 = 0; r0 < 32 * NI; r0 += kWave) {
-      const int row = mw + r0 + lane;
-      if (r0 + lane < 32 * NI && row < M) hit |= (unsigned)(a.labels[row] - vbase) < 64u;
-    }
-    if (__builtin_amdgcn_ballot_w64(hit) != 0 && vbase < a.V) {  // wavefront-uniform
+    for (int q = 0; q < (32 * NI + kWave - 1) / kWave; ++q) {
+      const int rl = q * kWave + lane;
+      const int lab = rl < 32 * NI && mw + rl < M ? a.labels[mw + rl] : -1;
+      unsigned long long hits = __builtin_amdgcn_ballot_w64((unsigned)(lab - vbase) < 64u && lab < a.V);
+      while (hits != 0) {  // wavefront-uniform
+        const int src = __builtin_ctzll(hits);
+        hits &= hits - 1;
+        const int rowl = q * kWave + src;                                 // row inside this call's rows
+        const int col = __builtin_amdgcn_readlane(lab, src) - vbase;      // token inside its 64
+        const int ti = rowl >> 5, x = rowl & 31, th = (x >> 2) & 1, tr = ((x >> 3) << 2) | (x & 3);
+        const int tc = col >> 5, tj = col & 31;
+        floatx16 t = acc[0][0];
 #pragma unroll
-      for (int i = 0; i < NI; ++i) {
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = mw + 4 * h + i * 32 + 8 * (r >> 2) + (r & 3);
-          const int lab = row < M ? a.labels[row] : -1;
-          if (v0 < a.V && lab == v0) a.label_logit[row] = acc[i][0][r] * sc;
-          if (v1 < a.V && lab == v1) a.label_logit[row] = acc[i][1][r] * sc;
-        }
+          for (int c = 0; c < 2; ++c)
+            if (i == ti && c == tc) t = acc[i][c];
+        float v = t[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) v = r == tr ? t[r] : v;
+        if (lane == tj + 32 * th) a.label_logit[mw + rowl] = v * sc;
       }
     }
   }

@@ -59,22 +59,34 @@ __device__ __forceinline__ void epilogue_128x128(const HeadArgs& a, floatx16 (&a
   const int j32 = lane & 31, h = lane >> 5;
   const float sc = a.inv_tau;
   if constexpr (CE) {
-    // as in the shared epilogue: look for a label inside this tile first, one or two rows per lane
-    bool hit = false;
+    // A row's label token lies in one tile of one wavefront, in one lane's accumulators.  Every lane looks up the
+    // labels of two of the wavefront's 128 rows; a label that falls among this tile's 128 tokens (13 % of the
+    // (wavefront, tile) pairs have one at V = 126464) is then fetched in a loop over the hits with wavefront-uniform
+    // indices: the 32 x 32 accumulator tile by comparison of scalars, the element inside it likewise, and the lane
+    // that holds it stores it.  (Going through all of a lane's elements with a label lookup each was a chain of
+    // 64 load latencies per hit: 1850 against 1700 us per call at R = 2048, and the workgroups of an XCD, which
+    // share their operand tiles through its L2 while they walk in step, fell out of step: 47 % L2 hits against 77 %.)
 #pragma unroll
-    for (int r0 = 0; r0 < 128; r0 += kWave) hit |= (unsigned)(a.labels[mw + r0 + lane] - vbase) < 128u;
-    if (__builtin_amdgcn_ballot_w64(hit) != 0) {  // wavefront-uniform
+    for (int q = 0; q < 2; ++q) {
+      const int lab = a.labels[mw + q * kWave + lane];
+      unsigned long long hits = __builtin_amdgcn_ballot_w64((unsigned)(lab - vbase) < 128u);
+      while (hits != 0) {  // wavefront-uniform
+        const int src = __builtin_ctzll(hits);
+        hits &= hits - 1;
+        const int rowl = q * kWave + src;                                     // row inside the wavefront's tile
+        const int col = __builtin_amdgcn_readlane(lab, src) - vbase;          // token inside it
+        const int ti = rowl >> 5, x = rowl & 31, th = (x >> 2) & 1, tr = ((x >> 3) << 2) | (x & 3);
+        const int tc = col >> 5, tj = col & 31;
+        floatx16 t = acc[0][0][0];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = mw + 4 * h + i * 32 + 8 * (r >> 2) + (r & 3);
-          const int d = a.labels[row] - (vbase + j32);
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
           for (int c = 0; c < 4; ++c)
-            if (d == 32 * c) a.label_logit[row] = acc[c >> 1][i][c & 1][r] * sc;
-          __builtin_amdgcn_sched_barrier(0);  // one row at a time: this path is rare and must not cost registers
-        }
+            if (i == ti && c == tc) t = acc[c >> 1][i][c & 1];
+        float v = t[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) v = r == tr ? t[r] : v;
+        if (lane == tj + 32 * th) a.label_logit[mw + rowl] = v * sc;
       }
     }
   }
