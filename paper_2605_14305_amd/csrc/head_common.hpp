@@ -195,15 +195,16 @@ __device__ __forceinline__ void store_logits_and_partials(const HeadArgs& a, flo
         const int col = __builtin_amdgcn_readlane(lab, src) - vbase;      // token inside its 64
         const int ti = rowl >> 5, x = rowl & 31, th = (x >> 2) & 1, tr = ((x >> 3) << 2) | (x & 3);
         const int tc = col >> 5, tj = col & 31;
-        floatx16 t = acc[0][0];
+        float v = 0.f;
 #pragma unroll
         for (int i = 0; i < NI; ++i)
 #pragma unroll
           for (int c = 0; c < 2; ++c)
-            if (i == ti && c == tc) t = acc[i][c];
-        float v = t[0];
+            if (i == ti && c == tc) {  // wavefront-uniform: one of the accumulator tiles
+              v = acc[i][c][0];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) v = r == tr ? t[r] : v;
+              for (int r = 1; r < 16; ++r) v = r == tr ? acc[i][c][r] : v;
+            }
         if (lane == tj + 32 * th) a.label_logit[mw + rowl] = v * sc;
       }
     }

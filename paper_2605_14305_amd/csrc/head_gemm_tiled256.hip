@@ -77,15 +77,16 @@ __device__ __forceinline__ void epilogue_128x128(const HeadArgs& a, floatx16 (&a
         const int col = __builtin_amdgcn_readlane(lab, src) - vbase;          // token inside it
         const int ti = rowl >> 5, x = rowl & 31, th = (x >> 2) & 1, tr = ((x >> 3) << 2) | (x & 3);
         const int tc = col >> 5, tj = col & 31;
-        floatx16 t = acc[0][0][0];
+        float v = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
           for (int c = 0; c < 4; ++c)
-            if (i == ti && c == tc) t = acc[c >> 1][i][c & 1];
-        float v = t[0];
+            if (i == ti && c == tc) {  // wavefront-uniform: one of the accumulator tiles
+              v = acc[c >> 1][i][c & 1][0];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) v = r == tr ? t[r] : v;
+              for (int r = 1; r < 16; ++r) v = r == tr ? acc[c >> 1][i][c & 1][r] : v;
+            }
         if (lane == tj + 32 * th) a.label_logit[mw + rowl] = v * sc;
       }
     }
