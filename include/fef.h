@@ -33,9 +33,9 @@
  *     says "host".  fef_params itself lives in host memory.
  *   - The library allocates nothing: scratch space is the caller's `workspace`
  *     (fef_workspace_bytes tells how much; fef_verify_step_static uses a buffer built into the
- *     library instead).  No result depends on an earlier call; the only things the library
- *     remembers are per-device constants it looks up once (the number of compute units, the
- *     address of the built-in buffer).
+ *     library instead).  No result depends on an earlier call; the only thing the library
+ *     remembers is a per-device constant it looks up once (the address of the built-in buffer).
+ *     The kernels' grids are sized for the 256 compute units of the device they are written for.
  *   - All work is enqueued on `stream`; the call returns without synchronising and the
  *     outputs are valid in stream order.  Concurrent calls need distinct workspaces.
  *   - Return value: FEF_OK or a negative fef_status.  Arguments are validated on the host
