@@ -287,7 +287,7 @@ __global__ __launch_bounds__(NT) void row_lse_draft_kernel(VerifyArgs a) {
     // lane); with many it loads tile j*64 + l, 512 contiguous bytes per instruction, and hands
     // each exp-sum to its owner through this wavefront's slice of LDS (rows of PER + 1 floats,
     // an odd stride, so both directions are conflict-free).
-    constexpr bool EXCHANGE = PER > 8;
+    constexpr bool EXCHANGE = PER > 10;
     __shared__ float exchange[EXCHANGE ? NW : 1][EXCHANGE ? kWave * (PER + 1) : 1];
     float2 p[PER];
 #pragma unroll
@@ -772,6 +772,7 @@ hipError_t launch_verify(const VerifyArgs& a) {
   const dim3 g1((a.nrows + NW - 1) / NW);
   if (a.nT <= 64 * 4) hipLaunchKernelGGL(row_lse_draft_kernel<4>, g1, dim3(NT), 0, a.stream, a);
   else if (a.nT <= 64 * 8) hipLaunchKernelGGL(row_lse_draft_kernel<8>, g1, dim3(NT), 0, a.stream, a);
+  else if (a.nT <= 64 * 10) hipLaunchKernelGGL(row_lse_draft_kernel<10>, g1, dim3(NT), 0, a.stream, a);  // 594 tiles of 256 tokens: V = 151936
   else if (a.nT <= 64 * 40) hipLaunchKernelGGL(row_lse_draft_kernel<40>, g1, dim3(NT), 0, a.stream, a);
   else hipLaunchKernelGGL(row_lse_draft_kernel<0>, g1, dim3(NT), 0, a.stream, a);
   if (a.phase == 3) {
